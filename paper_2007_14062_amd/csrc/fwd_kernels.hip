@@ -11,6 +11,8 @@
 // from LDS in the matching permuted key order).
 #include "fwd_kernels.h"
 
+#include <cstdio>
+
 namespace bb {
 
 namespace {
@@ -344,6 +346,16 @@ __global__ __launch_bounds__(256) void fwd_combine_kernel(FwdParams p) {
   }
 }
 
+namespace {
+// Reports a failed launch on stderr (the status code cannot carry the runtime's reason).
+bool launch_failed(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return false;
+  fprintf(stderr, "bigbird: launch of %s failed: %s\n", what, hipGetErrorString(e));
+  return true;
+}
+}  // namespace
+
 int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream) {
   const RowSplit& s = p.split;
   const unsigned grid = static_cast<unsigned>(kXcd) * s.bh_rounds * s.items_per_bh;
@@ -352,7 +364,7 @@ int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream) {
     hipLaunchKernelGGL(fwd_kernel<true>, dim3(grid), dim3(kThreads), 0, stream, p);
   else
     hipLaunchKernelGGL(fwd_kernel<false>, dim3(grid), dim3(kThreads), 0, stream, p);
-  if (hipGetLastError() != hipSuccess) return BB_ERR_LAUNCH;
+  if (launch_failed("fwd_kernel")) return BB_ERR_LAUNCH;
   const int rows_per_bh = (s.cg > 1 ? p.g : 0) + (s.cs > 1 ? p.nb - p.g : 0);
   if (rows_per_bh > 0) {
     const unsigned cgrid = static_cast<unsigned>(p.BH) * rows_per_bh;
@@ -360,7 +372,7 @@ int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream) {
       hipLaunchKernelGGL(fwd_combine_kernel<true>, dim3(cgrid), dim3(256), 0, stream, p);
     else
       hipLaunchKernelGGL(fwd_combine_kernel<false>, dim3(cgrid), dim3(256), 0, stream, p);
-    if (hipGetLastError() != hipSuccess) return BB_ERR_LAUNCH;
+    if (launch_failed("fwd_combine_kernel")) return BB_ERR_LAUNCH;
   }
   return BB_OK;
 }
