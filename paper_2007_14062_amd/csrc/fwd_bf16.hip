@@ -1,0 +1,257 @@
+// bf16 forward kernel: the tuned path of the BERT-shaped workloads.
+//
+// Same mathematics as the fp32 kernel (eq. (AT) per head on the App. D pattern),
+// with the machinery the bf16 MFMA rate asks for:
+//   * K and V tiles go global -> LDS directly (no registers in between), one
+//     buffer each; a tile is read out into MFMA operand registers at once, so the
+//     buffer is free again and the next tile's load overlaps the arithmetic;
+//   * V^T operands come from the transposing LDS read;
+//   * the softmax reference exponent moves only when a row maximum grows by more
+//     than 2^8, so the accumulator rescale is rare; row sums are taken from the
+//     bf16-rounded probabilities with the packed dot instruction.
+#include "fwd_epilogue.h"
+
+#include <cstdio>
+
+namespace bb {
+
+namespace {
+
+constexpr float kLazyLog2 = 8.f;  // rescale when a row maximum grows by more than 2^8
+
+// s_waitcnt immediate that waits for all but `n` vector-memory loads (gfx9 encoding:
+// vmcnt in bits 3:0 and 15:14, other counters left at their maxima).
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+constexpr int kLgkmcnt0 = 15 | (3 << 14) | (7 << 4);  // wait for all LDS reads, nothing else
+
+// Enqueue this wave's half of a 64x64 bf16 tile: global -> LDS, 16 bytes per lane,
+// four instructions per wave.  Instruction ii of wave wv fills LDS rows
+// 8*(2*ii+wv) .. +8 linearly (the hardware places lane l at M0 + 16*l), so the XOR
+// swizzle is applied on the global side: the lane that lands on chunk position p of
+// row r fetches chunk p ^ (r & 7).  `voff` is that per-lane byte offset inside the
+// tile (fixed for the kernel), `gtile` the wave-uniform tile address, `lds` the
+// LDS byte address of this wave's first 1 KB slot.
+// Written as inline asm so that the compiler's wait-count bookkeeping does not see
+// these loads: it would otherwise drain them before every LDS read.  The waits
+// are placed by hand (loads return in order, so vmcnt(N) is exact).
+__device__ __forceinline__ void tile_load_async(const char* gtile, unsigned lds, unsigned voff) {
+#pragma unroll
+  for (int ii = 0; ii < 4; ++ii)
+    asm volatile(
+        "s_mov_b32 m0, %2\n\t"
+        "global_load_lds_dwordx4 %0, %1"
+        :
+        : "v"(voff + ii * 2048), "s"(gtile), "s"(lds + ii * 2048)
+        : "memory");  // M0 is written here; nothing else in this kernel reads M0
+}
+
+__device__ __forceinline__ unsigned lds_addr(const void* p) {
+  return static_cast<unsigned>(reinterpret_cast<uintptr_t>((BB_LDS const char*)(p)));
+}
+
+}  // namespace
+
+#ifndef BB_FWD_WAVES_PER_EU
+#define BB_FWD_WAVES_PER_EU 3
+#endif
+
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would
+// drain the LDS-bound loads still in flight.  Ordering is kept by the explicit
+// counter waits next to each use; the empty asm stops compiler reordering.
+#define BB_BARRIER()                       \
+  do {                                     \
+    asm volatile("" ::: "memory");         \
+    __builtin_amdgcn_s_barrier();          \
+    asm volatile("" ::: "memory");         \
+  } while (0)
+
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(BB_FWD_WAVES_PER_EU)))
+void fwd_kernel_bf16(FwdParams p) {
+  __shared__ __attribute__((aligned(1024))) char lds_k[kBlk * kDim * 2];
+  __shared__ __attribute__((aligned(1024))) char lds_v[kBlk * kDim * 2];
+  __shared__ int klist[kChunk];
+
+  const Pattern pat{p.nb, p.g, p.w, p.global_mode};
+  WorkItem it;
+  if (!decode_item(p.split, pat, p.BH, blockIdx.x, &it)) return;
+  const int bi = it.bh / p.H, h = it.bh % p.H;
+  const int lane = lane_id(), wv = threadIdx.x >> 6;
+  const int hf = lane >> 5, col = lane & 31;
+
+  const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
+                                 it.chunk, klist);
+  __syncthreads();
+
+  const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
+  const size_t qrow = bh_row0 + it.j * kBlk + wv * 32 + col;
+  const char* kbase = static_cast<const char*>(p.K) + bh_row0 * (kDim * 2);
+  const char* vbase = static_cast<const char*>(p.V) + bh_row0 * (kDim * 2);
+
+  // per-lane pieces of the tile loads (see tile_load_async)
+  const unsigned voff = ((wv * 8 + (lane >> 3)) * 128) + ((((lane & 7) ^ (lane >> 3))) << 4);
+  const unsigned lds_k_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_k) + wv * 1024);
+  const unsigned lds_v_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_v) + wv * 1024);
+  if (cnt > 0) {
+    const size_t off = static_cast<size_t>(__builtin_amdgcn_readfirstlane(klist[0])) * (kBlk * kDim * 2);
+    tile_load_async(kbase + off, lds_k_wave, voff);
+    tile_load_async(vbase + off, lds_v_wave, voff);
+  }
+
+  // Q^T operand (B of S^T = K Q^T): lane holds query `col`, d = 16*ks + 8*hf .. +8
+  bf16x8 qb[4];
+  {
+    const bf16x8* qp = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.Q) + qrow * kDim);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qb[ks] = qp[ks * 2 + hf];
+  }
+
+  // Make the compiler account for the Q loads here, once, instead of at the first
+  // use inside the loop (where its conservative wait would drain the tile loads).
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qb[ks]));
+
+  f32x16 o[2];
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+  float m_ref = neg_inf();  // reference exponent in raw score units (both halves agree)
+  float l_run = 0.f;        // this lane's share of sum 2^((s - m_ref) c)
+  const float c = p.c;
+  const float tau = kLazyLog2 / c;
+
+  // LDS byte offsets of this lane's operand pieces (fixed for the whole item)
+  int koff[2][4];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) koff[t][ks] = tile_off_bf16(t * 32 + col, ks * 2 + hf);
+  const int gq = lane >> 4, li = lane & 15;
+
+  for (int i = 0; i < cnt; ++i) {
+    const int kb = klist[i];
+    const bool more = i + 1 < cnt;
+    size_t next_off = 0;
+    if (more)
+      next_off = static_cast<size_t>(__builtin_amdgcn_readfirstlane(klist[i + 1])) * (kBlk * kDim * 2);
+    uint64_t vbits = ~0ull;
+    if (p.kmask) vbits = key_valid_bits(p.kmask, bi, p.n, kb);
+
+    // ---- K tile landed?  (the V loads of this block were issued after it: 4 may be in flight)
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+    BB_BARRIER();
+    bf16x8 ka[2][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks)
+        ka[t][ks] = *reinterpret_cast<const bf16x8*>(lds_k + koff[t][ks]);
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+    BB_BARRIER();  // both waves hold their K operands: the buffer is free
+    if (more) tile_load_async(kbase + next_off, lds_k_wave, voff);
+
+    // ---- S^T = K Q^T: rows = 64 keys (two MFMA tiles), columns = this wave's 32 queries
+    f32x16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], s[t], 0, 0, 0);
+
+    if (vbits != ~0ull) {  // partly padded block: masked keys get -inf
+      const uint64_t mine = vbits >> (hf * 4);
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (!((mine >> (t * 32 + acc_row(r, 0))) & 1)) s[t][r] = neg_inf();
+    }
+
+    // ---- online softmax, base 2, lazily moved reference
+    float mloc = neg_inf();
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[t][r]);
+    mloc = half_max(mloc);
+    if (__any(mloc > m_ref + tau)) {
+      const float m_new = fmaxf(m_ref, mloc);
+      const float m_use = (m_new == neg_inf()) ? 0.f : m_new;
+      const float alpha = fast_exp2((m_ref - m_use) * c);
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+      m_ref = m_new;
+    }
+    const float mc = (m_ref == neg_inf()) ? 0.f : m_ref * c;
+    bf16x8 pb[4];
+    const bf16x2 ones = {static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)};
+#pragma unroll
+    for (int sg = 0; sg < 4; ++sg)
+#pragma unroll
+      for (int kk = 0; kk < 8; kk += 2) {
+        const int t = sg >> 1, r = (sg & 1) * 8 + kk;
+        const float p0 = fast_exp2(__builtin_fmaf(s[t][r], c, -mc));
+        const float p1 = fast_exp2(__builtin_fmaf(s[t][r + 1], c, -mc));
+        const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+        pb[sg][kk] = pk[0];
+        pb[sg][kk + 1] = pk[1];
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
+      }
+
+    // ---- V tile landed?  (if a K load for the next block was issued, 4 may be in flight)
+    if (more)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    BB_BARRIER();
+    // V^T operand (A of O^T += V^T P^T): lane holds d = 32*dt + col and, in MFMA
+    // contraction slot 8*hf + kk, the key 16*sg + 4*hf + kk (kk < 4) or + 8 + kk - 4.
+    bf16x8 va[2][4];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt) {
+      const int chunk = dt * 4 + (gq & 1) * 2 + ((li & 3) >> 1);
+      const int sub = (li & 1) * 8;
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        const int row1 = sg * 16 + hf * 4 + (li >> 2);
+        const s16x4 lo = lds_read_tr16(lds_v + tile_off_bf16(row1, chunk) + sub);
+        const s16x4 hi = lds_read_tr16(lds_v + tile_off_bf16(row1 + 8, chunk) + sub);
+        union { struct { s16x4 a, b; } h2; bf16x8 v; } u;
+        u.h2.a = lo;
+        u.h2.b = hi;
+        va[dt][sg] = u.v;
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+    BB_BARRIER();  // both waves hold their V operands
+    if (more) tile_load_async(vbase + next_off, lds_v_wave, voff);
+
+#pragma unroll
+    for (int sg = 0; sg < 4; ++sg)
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pb[sg], o[dt], 0, 0, 0);
+  }
+
+  const float l_tot = half_sum(l_run);
+  fwd_store<true>(p, it, o, m_ref, l_tot, c, qrow, wv * 32 + col, hf);
+}
+
+int launch_fwd_bf16_main(const FwdParams& p, unsigned grid, hipStream_t stream) {
+  hipLaunchKernelGGL(fwd_kernel_bf16, dim3(grid), dim3(kThreads), 0, stream, p);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) {
+    fprintf(stderr, "bigbird: launch of fwd_kernel_bf16 failed: %s\n", hipGetErrorString(e));
+    return BB_ERR_LAUNCH;
+  }
+  return BB_OK;
+}
+
+}  // namespace bb

@@ -24,5 +24,8 @@ struct FwdParams {
 // Enqueues the fused forward kernel and, if any row is split, the merge kernel.
 int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream);
 
+// The tuned bf16 main kernel (defined in fwd_bf16.hip); launch_fwd calls it.
+int launch_fwd_bf16_main(const FwdParams& p, unsigned grid, hipStream_t stream);
+
 }  // namespace bb
 #endif  // BB_FWD_KERNELS_H_
