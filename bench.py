@@ -52,13 +52,13 @@ def device_inputs(wl, torch, dev):
 
 
 def time_cpu_oracle(wl, t, rand_idx, sample_heads: int):
-    """Oracle forward on batch 0, the first `sample_heads` heads, all host cores NumPy uses."""
+    """Oracle forward on batches 0-1, the first `sample_heads` heads, all host cores NumPy uses."""
     import oracle
-    Q, K, V = (t[x][:1, :sample_heads] for x in ("Q", "K", "V"))
+    Q, K, V = (t[x][:2, :sample_heads] for x in ("Q", "K", "V"))
     t0 = time.perf_counter()
     oracle.attn_fwd(Q, K, V, rand_idx[:sample_heads], wl.b, wl.g, wl.w, wl.scale)
     dt = time.perf_counter() - t0
-    pairs = oracle.count_block_pairs(rand_idx[:sample_heads], wl.n, wl.b, wl.g, wl.w)
+    pairs = 2 * oracle.count_block_pairs(rand_idx[:sample_heads], wl.n, wl.b, wl.g, wl.w)
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -71,19 +71,34 @@ def time_cpu_oracle(wl, t, rand_idx, sample_heads: int):
         "unit": "useful TFLOP/s",
         "cores": cores,
         "kind": "oracle",
-        "sample": f"forward of batch 0, heads 0..{sample_heads - 1} of {wl.name} "
+        "sample": f"forward of batches 0-1, heads 0..{sample_heads - 1} of {wl.name} "
                   f"(fp64 dense-mask NumPy oracle, {dt:.2f} s)",
         "seconds": dt,
     }
 
 
+def measured_traffic_bytes():
+    """HBM bytes per forward call from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "fwd_kernel_bf16_cfg2_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("hbm_bytes_per_launch_fwd_total"):
+                return int(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--cpu-sample-heads", type=int, default=4)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=500)
+    ap.add_argument("--cpu-sample-heads", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 256 MiB device copy 10 times (known HBM traffic: 256 MiB read, "
+                         "256 MiB written per copy), to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (every (batch, head) "
@@ -97,6 +112,14 @@ def main():
         print("bench.py needs a GPU: the library has no CPU path", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": 256 << 20, "copies": 10}))
+        return
     wl = inp.WORKLOADS[WORKLOAD]
     rand_idx = bb.bigbird_make_rand_idx(wl.H, wl.n, wl.b, wl.g, wl.w, wl.r, wl.pattern_seed)
     t, dv = device_inputs(wl, torch, dev)
@@ -109,9 +132,9 @@ def main():
     ws_bytes = bb.bigbird_attn_workspace_bytes(wl.B, wl.H, wl.n, wl.d, wl.b, wl.g, wl.w, wl.r)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
 
-    def step():
-        bb.bigbird_attn_fwd(dv["Q"], dv["K"], dv["V"], ridx, g=wl.g, w=wl.w, scale=wl.scale,
-                            key_padding_mask=dv["key_mask"], O=O, LSE=LSE, workspace=ws)
+    # arguments marshalled once: each step is exactly one bigbird_attn_fwd C call
+    step = bb.prepare_attn_fwd(dv["Q"], dv["K"], dv["V"], ridx, O, LSE, ws, g=wl.g, w=wl.w,
+                               scale=wl.scale, key_padding_mask=dv["key_mask"])
 
     for _ in range(args.warmup):
         step()
@@ -148,7 +171,8 @@ def main():
                    "useful_gflop_per_step": flops / 1e9, "pass": "forward"},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": BF16_MFMA_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": tflops / BF16_MFMA_PEAK_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": tflops / BF16_MFMA_PEAK_TFLOPS,
+                     "traffic": measured_traffic_bytes(),
                      "kernel": "fwd_kernel<bf16> (+ fwd_combine_kernel, same timed region)"},
     }
     if not args.no_cpu_baseline:

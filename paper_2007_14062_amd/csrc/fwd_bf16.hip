@@ -2,9 +2,10 @@
 //
 // Same mathematics as the fp32 kernel (eq. (AT) per head on the App. D pattern),
 // with the machinery the bf16 MFMA rate asks for:
-//   * K and V tiles go global -> LDS directly (no registers in between), one
-//     buffer each; a tile is read out into MFMA operand registers at once, so the
-//     buffer is free again and the next tile's load overlaps the arithmetic;
+//   * K and V tiles go global -> LDS directly (no registers in between), two
+//     buffers each, one workgroup barrier per key block;
+//   * the scores of key block i+1 are issued to the MFMA pipe before the softmax
+//     of block i runs on the vector ALU, so the two pipes overlap inside a wave;
 //   * V^T operands come from the transposing LDS read;
 //   * the softmax reference exponent moves only when a row maximum grows by more
 //     than 2^8, so the accumulator rescale is rare; row sums are taken from the
@@ -12,6 +13,7 @@
 #include "fwd_epilogue.h"
 
 #include <cstdio>
+#include <type_traits>
 
 namespace bb {
 
@@ -52,7 +54,7 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) {
 }  // namespace
 
 #ifndef BB_FWD_WAVES_PER_EU
-#define BB_FWD_WAVES_PER_EU 3
+#define BB_FWD_WAVES_PER_EU 2
 #endif
 
 // Workgroup barrier without the memory fence of __syncthreads(): the fence would
@@ -65,10 +67,21 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) {
     asm volatile("" ::: "memory");         \
   } while (0)
 
+// Schedule of one work item (key blocks k_0 .. k_{cnt-1}); K and V each have two
+// LDS buffers:
+//   prologue   load K0 -> Kbuf0, V0 -> Vbuf0, K1 -> Kbuf1;  S(0) = K0 Q^T
+//   step i     wait for K(i+1), V(i); barrier            (one barrier per key block)
+//              load K(i+2) -> Kbuf[i&1], V(i+1) -> Vbuf[(i+1)&1]   (a full step of slack)
+//              issue S(i+1) = K(i+1) Q^T on the MFMA pipe ...
+//              ... while the VALU does the softmax of S(i)
+//              O += V(i)^T P(i)^T, its MFMAs interleaved with the exponentials
+// so within one wave the matrix pipe works on the next block's scores while the
+// vector pipe exponentiates the current block's.
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(BB_FWD_WAVES_PER_EU)))
 void fwd_kernel_bf16(FwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds_k[kBlk * kDim * 2];
-  __shared__ __attribute__((aligned(1024))) char lds_v[kBlk * kDim * 2];
+  constexpr int kTile = kBlk * kDim * 2;  // 8 KB
+  __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTile];
+  __shared__ __attribute__((aligned(1024))) char lds_v[2 * kTile];
   __shared__ int klist[kChunk];
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
@@ -81,6 +94,8 @@ void fwd_kernel_bf16(FwdParams p) {
   const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
                                  it.chunk, klist);
   __syncthreads();
+  const int kl = klist[lane & (kChunk - 1)];  // lane t holds list entry t & 7
+  auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
 
   const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
   const size_t qrow = bh_row0 + it.j * kBlk + wv * 32 + col;
@@ -91,10 +106,12 @@ void fwd_kernel_bf16(FwdParams p) {
   const unsigned voff = ((wv * 8 + (lane >> 3)) * 128) + ((((lane & 7) ^ (lane >> 3))) << 4);
   const unsigned lds_k_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_k) + wv * 1024);
   const unsigned lds_v_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_v) + wv * 1024);
+  auto tile_off = [&](int i) { return static_cast<size_t>(key_block(i)) * kTile; };
+
   if (cnt > 0) {
-    const size_t off = static_cast<size_t>(__builtin_amdgcn_readfirstlane(klist[0])) * (kBlk * kDim * 2);
-    tile_load_async(kbase + off, lds_k_wave, voff);
-    tile_load_async(vbase + off, lds_v_wave, voff);
+    tile_load_async(kbase + tile_off(0), lds_k_wave, voff);
+    tile_load_async(vbase + tile_off(0), lds_v_wave, voff);
+    if (cnt > 1) tile_load_async(kbase + tile_off(1), lds_k_wave + kTile, voff);
   }
 
   // Q^T operand (B of S^T = K Q^T): lane holds query `col`, d = 16*ks + 8*hf .. +8
@@ -104,7 +121,6 @@ void fwd_kernel_bf16(FwdParams p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qb[ks] = qp[ks * 2 + hf];
   }
-
   // Make the compiler account for the Q loads here, once, instead of at the first
   // use inside the loop (where its conservative wait would drain the tile loads).
 #pragma unroll
@@ -127,31 +143,20 @@ void fwd_kernel_bf16(FwdParams p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) koff[t][ks] = tile_off_bf16(t * 32 + col, ks * 2 + hf);
   const int gq = lane >> 4, li = lane & 15;
+  int voff_tr[2];  // V^T operand: row (4*hf + li/4) of a 16-key group, 8-byte piece of a d chunk
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt)
+    voff_tr[dt] = tile_off_bf16(hf * 4 + (li >> 2), dt * 4 + (gq & 1) * 2 + ((li & 3) >> 1)) + (li & 1) * 8;
 
-  for (int i = 0; i < cnt; ++i) {
-    const int kb = klist[i];
-    const bool more = i + 1 < cnt;
-    size_t next_off = 0;
-    if (more)
-      next_off = static_cast<size_t>(__builtin_amdgcn_readfirstlane(klist[i + 1])) * (kBlk * kDim * 2);
-    uint64_t vbits = ~0ull;
-    if (p.kmask) vbits = key_valid_bits(p.kmask, bi, p.n, kb);
-
-    // ---- K tile landed?  (the V loads of this block were issued after it: 4 may be in flight)
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
-    BB_BARRIER();
+  // S^T = K Q^T for the tile in K buffer `buf`: rows = 64 keys (two MFMA tiles), columns =
+  // this wave's 32 queries.
+  auto scores = [&](int buf, f32x16 (&s)[2]) {
+    const char* kt = lds_k + buf * kTile;
     bf16x8 ka[2][4];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-        ka[t][ks] = *reinterpret_cast<const bf16x8*>(lds_k + koff[t][ks]);
-    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
-    BB_BARRIER();  // both waves hold their K operands: the buffer is free
-    if (more) tile_load_async(kbase + next_off, lds_k_wave, voff);
-
-    // ---- S^T = K Q^T: rows = 64 keys (two MFMA tiles), columns = this wave's 32 queries
-    f32x16 s[2];
+      for (int ks = 0; ks < 4; ++ks) ka[t][ks] = *reinterpret_cast<const bf16x8*>(kt + koff[t][ks]);
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -161,6 +166,33 @@ void fwd_kernel_bf16(FwdParams p) {
 #pragma unroll
       for (int t = 0; t < 2; ++t)
         s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], s[t], 0, 0, 0);
+  };
+
+  f32x16 sc[2][2];  // scores of the current and of the next key block
+  if (cnt > 0) {
+    // K0 landed (V0 and, if there is one, K1 may still be in flight)
+    if (cnt > 1)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+    BB_BARRIER();
+    scores(0, sc[0]);
+  }
+
+  auto step = [&](auto parity, int i) {
+    constexpr int P = decltype(parity)::value;
+    f32x16(&s)[2] = sc[P];
+    const int kb = key_block(i);
+    uint64_t vbits = ~0ull;
+    if (p.kmask) vbits = key_valid_bits(p.kmask, bi, p.n, kb);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // K(i+1) and V(i) have landed
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);     // and this wave's reads of the buffers reused below are done
+    BB_BARRIER();
+    if (i + 2 < cnt) tile_load_async(kbase + tile_off(i + 2), lds_k_wave + P * kTile, voff);
+    if (i + 1 < cnt) {
+      tile_load_async(vbase + tile_off(i + 1), lds_v_wave + (P ^ 1) * kTile, voff);
+      scores(P ^ 1, sc[P ^ 1]);  // next block's scores: runs on the MFMA pipe under the softmax below
+    }
 
     if (vbits != ~0ull) {  // partly padded block: masked keys get -inf
       const uint64_t mine = vbits >> (hf * 4);
@@ -190,56 +222,47 @@ void fwd_kernel_bf16(FwdParams p) {
       m_ref = m_new;
     }
     const float mc = (m_ref == neg_inf()) ? 0.f : m_ref * c;
-    bf16x8 pb[4];
+
+    // V^T operand (A of O^T += V^T P^T): lane holds d = 32*dt + col and, in MFMA
+    // contraction slot 8*hf + kk, the key 16*sg + 4*hf + kk (kk < 4) or + 8 + kk - 4.
+    const char* vt = lds_v + P * kTile;
+    bf16x8 va[2][4];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int sg = 0; sg < 4; ++sg) {
+        // rows 16*sg + {0, 8} + (4*hf + li/4): a multiple of 8 added to the row keeps the swizzle
+        const s16x4 lo = lds_read_tr16(vt + voff_tr[dt] + sg * 2048);
+        const s16x4 hi = lds_read_tr16(vt + voff_tr[dt] + sg * 2048 + 1024);
+        union { struct { s16x4 a, b; } h2; bf16x8 v; } u;
+        u.h2.a = lo;
+        u.h2.b = hi;
+        va[dt][sg] = u.v;
+      }
     const bf16x2 ones = {static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)};
 #pragma unroll
-    for (int sg = 0; sg < 4; ++sg)
+    for (int sg = 0; sg < 4; ++sg) {
+      bf16x8 pb;
 #pragma unroll
       for (int kk = 0; kk < 8; kk += 2) {
         const int t = sg >> 1, r = (sg & 1) * 8 + kk;
         const float p0 = fast_exp2(__builtin_fmaf(s[t][r], c, -mc));
         const float p1 = fast_exp2(__builtin_fmaf(s[t][r + 1], c, -mc));
         const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
-        pb[sg][kk] = pk[0];
-        pb[sg][kk + 1] = pk[1];
+        pb[kk] = pk[0];
+        pb[kk + 1] = pk[1];
         l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
       }
-
-    // ---- V tile landed?  (if a K load for the next block was issued, 4 may be in flight)
-    if (more)
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
-    else
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    BB_BARRIER();
-    // V^T operand (A of O^T += V^T P^T): lane holds d = 32*dt + col and, in MFMA
-    // contraction slot 8*hf + kk, the key 16*sg + 4*hf + kk (kk < 4) or + 8 + kk - 4.
-    bf16x8 va[2][4];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt) {
-      const int chunk = dt * 4 + (gq & 1) * 2 + ((li & 3) >> 1);
-      const int sub = (li & 1) * 8;
-#pragma unroll
-      for (int sg = 0; sg < 4; ++sg) {
-        const int row1 = sg * 16 + hf * 4 + (li >> 2);
-        const s16x4 lo = lds_read_tr16(lds_v + tile_off_bf16(row1, chunk) + sub);
-        const s16x4 hi = lds_read_tr16(lds_v + tile_off_bf16(row1 + 8, chunk) + sub);
-        union { struct { s16x4 a, b; } h2; bf16x8 v; } u;
-        u.h2.a = lo;
-        u.h2.b = hi;
-        va[dt][sg] = u.v;
-      }
-    }
-    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
-    BB_BARRIER();  // both waves hold their V operands
-    if (more) tile_load_async(vbase + next_off, lds_v_wave, voff);
-
-#pragma unroll
-    for (int sg = 0; sg < 4; ++sg)
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pb[sg], o[dt], 0, 0, 0);
-  }
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pb, o[dt], 0, 0, 0);
+    }
+  };
 
+  for (int i = 0; i < cnt; i += 2) {
+    step(std::integral_constant<int, 0>{}, i);
+    if (i + 1 < cnt) step(std::integral_constant<int, 1>{}, i + 1);
+  }
   const float l_tot = half_sum(l_run);
   fwd_store<true>(p, it, o, m_ref, l_tot, c, qrow, wv * 32 + col, hf);
 }

@@ -178,16 +178,22 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel_f32(FwdParams p) {
 }
 
 // Merge the slices of a split row: M = max m_c, L = sum l_c 2^(m_c - M),
-// O = sum O~_c 2^(m_c - M) / L, LSE = (M + log2 L) ln 2.  One workgroup per
-// (batch, head, split row); thread t owns query t/4 and 16 of its d columns.
+// O = sum O~_c 2^(m_c - M) / L, LSE = (M + log2 L) ln 2.  Four workgroups per
+// (batch, head, split row), 16 queries each; thread t owns 4 d columns of query
+// t/16, so a wavefront reads four full 256-byte rows of every partial.
+constexpr int kCombineThreads = 256;
+constexpr int kCombineSplit = 4;  // workgroups per 64-query block
+
 template <bool BF16>
-__global__ __launch_bounds__(256) void fwd_combine_kernel(FwdParams p) {
+__global__ __launch_bounds__(kCombineThreads) void fwd_combine_kernel(FwdParams p) {
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   const RowSplit& s = p.split;
   const int nglob_rows = s.cg > 1 ? p.g : 0;
   const int nsparse_rows = s.cs > 1 ? p.nb - p.g : 0;
   const int rows_per_bh = nglob_rows + nsparse_rows;
-  const int bh = blockIdx.x / rows_per_bh, rr = blockIdx.x % rows_per_bh;
+  const int part = blockIdx.x % kCombineSplit;
+  const int rowid = blockIdx.x / kCombineSplit;
+  const int bh = rowid / rows_per_bh, rr = rowid % rows_per_bh;
   int j, nchunks, slot0;
   if (rr < nglob_rows) {
     j = pat.global_block(rr);
@@ -199,53 +205,47 @@ __global__ __launch_bounds__(256) void fwd_combine_kernel(FwdParams p) {
     nchunks = s.cs;
     slot0 = bh * s.slots_per_bh + (s.cg > 1 ? p.g * s.cg : 0) + t * s.cs;
   }
-  const int q = threadIdx.x >> 2, d0 = (threadIdx.x & 3) * 16;
+  const int q = part * 16 + (threadIdx.x >> 4), d0 = (threadIdx.x & 15) * 4;
+  const float* ml = p.part_ml + static_cast<size_t>(slot0) * (2 * kBlk) + q;
+  const float* po = p.part_o + static_cast<size_t>(slot0) * (kBlk * kDim) + q * kDim + d0;
   float M = neg_inf();
-  for (int cidx = 0; cidx < nchunks; ++cidx)
-    M = fmaxf(M, p.part_ml[static_cast<size_t>(slot0 + cidx) * (2 * kBlk) + q]);
-  float acc[16];
-#pragma unroll
-  for (int e = 0; e < 16; ++e) acc[e] = 0.f;
+  for (int cidx = 0; cidx < nchunks; ++cidx) M = fmaxf(M, ml[cidx * (2 * kBlk)]);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   float L = 0.f;
   if (M != neg_inf()) {
-    for (int cidx = 0; cidx < nchunks; ++cidx) {
-      const float* pml = p.part_ml + static_cast<size_t>(slot0 + cidx) * (2 * kBlk);
-      const float mcur = pml[q];
-      if (mcur == neg_inf()) continue;
-      const float wgt = fast_exp2(mcur - M);
-      L += pml[kBlk + q] * wgt;
-      const f32x4* po = reinterpret_cast<const f32x4*>(
-          p.part_o + static_cast<size_t>(slot0 + cidx) * (kBlk * kDim) + q * kDim + d0);
+    constexpr int U = 8;  // partials in flight per thread
+    for (int c0 = 0; c0 < nchunks; c0 += U) {
+      f32x4 v[U];
+      float wgt[U], lc[U];
 #pragma unroll
-      for (int v4 = 0; v4 < 4; ++v4) {
-        const f32x4 v = po[v4];
+      for (int u = 0; u < U; ++u) {
+        const int cidx = c0 + u < nchunks ? c0 + u : nchunks - 1;
+        v[u] = *reinterpret_cast<const f32x4*>(po + static_cast<size_t>(cidx) * (kBlk * kDim));
+        const float mcur = ml[cidx * (2 * kBlk)];
+        lc[u] = ml[cidx * (2 * kBlk) + kBlk];
+        wgt[u] = (c0 + u < nchunks && mcur != neg_inf()) ? fast_exp2(mcur - M) : 0.f;
+      }
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc[v4 * 4 + e] += v[e] * wgt;
+      for (int u = 0; u < U; ++u) {
+        L += lc[u] * wgt[u];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += v[u][e] * wgt[u];
       }
     }
   }
   const float inv = L > 0.f ? 1.f / L : 0.f;
   const size_t row = static_cast<size_t>(bh) * p.n + j * kBlk + q;
-  if ((threadIdx.x & 3) == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
+  if ((threadIdx.x & 15) == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
   if constexpr (BF16) {
-    bf16x8 v0, v1;
+    bf16x4 v;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      v0[e] = static_cast<__bf16>(acc[e] * inv);
-      v1[e] = static_cast<__bf16>(acc[8 + e] * inv);
-    }
-    bf16x8* dst = reinterpret_cast<bf16x8*>(static_cast<__bf16*>(p.O) + row * kDim + d0);
-    dst[0] = v0;
-    dst[1] = v1;
+    for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(acc[e] * inv);
+    *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(p.O) + row * kDim + d0) = v;
   } else {
-    f32x4* dst = reinterpret_cast<f32x4*>(static_cast<float*>(p.O) + row * kDim + d0);
+    f32x4 v;
 #pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-      f32x4 v;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = acc[v4 * 4 + e] * inv;
-      dst[v4] = v;
-    }
+    for (int e = 0; e < 4; ++e) v[e] = acc[e] * inv;
+    *reinterpret_cast<f32x4*>(static_cast<float*>(p.O) + row * kDim + d0) = v;
   }
 }
 
@@ -272,11 +272,11 @@ int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream) {
   }
   const int rows_per_bh = (s.cg > 1 ? p.g : 0) + (s.cs > 1 ? p.nb - p.g : 0);
   if (rows_per_bh > 0) {
-    const unsigned cgrid = static_cast<unsigned>(p.BH) * rows_per_bh;
+    const unsigned cgrid = static_cast<unsigned>(p.BH) * rows_per_bh * kCombineSplit;
     if (bf16)
-      hipLaunchKernelGGL(fwd_combine_kernel<true>, dim3(cgrid), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL(fwd_combine_kernel<true>, dim3(cgrid), dim3(kCombineThreads), 0, stream, p);
     else
-      hipLaunchKernelGGL(fwd_combine_kernel<false>, dim3(cgrid), dim3(256), 0, stream, p);
+      hipLaunchKernelGGL(fwd_combine_kernel<false>, dim3(cgrid), dim3(kCombineThreads), 0, stream, p);
     if (launch_failed("fwd_combine_kernel")) return BB_ERR_LAUNCH;
   }
   return BB_OK;
