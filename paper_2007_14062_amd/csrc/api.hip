@@ -1,5 +1,6 @@
 // C ABI entry points: host-side checks, workspace carving, kernel launches.
 #include "bigbird.h"
+#include "bwd_kernels.h"
 #include "fwd_kernels.h"
 
 #include <cmath>
@@ -11,6 +12,10 @@ inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WorkspaceLayout {
   size_t part_o = 0, part_ml = 0;  // forward: partial triples of split rows
+  size_t fwd_total = 0;
+  // backward (its own carving of the same buffer): row sums, scaled LSE, partial gradients
+  size_t dvec = 0, lvec = 0, part_dq = 0, part_dk = 0, part_dv = 0;
+  size_t bwd_total = 0;
   size_t total = 0;
 };
 
@@ -34,8 +39,26 @@ WorkspaceLayout make_layout(int B, int H, int n, int b, int g, int w, int r, int
   off += round_up(slots * bb::kBlk * bb::kDim * sizeof(float));
   L.part_ml = off;
   off += round_up(slots * 2 * bb::kBlk * sizeof(float));
-  (void)need_bwd;
+  L.fwd_total = off;
   L.total = off;
+  if (need_bwd) {
+    const size_t rows = static_cast<size_t>(BH) * n;
+    const int cq = (nb + bb::kChunk - 1) / bb::kChunk;
+    const size_t kv_slots = cq > 1 ? static_cast<size_t>(BH) * g * cq : 0;
+    size_t o2 = 0;
+    L.dvec = o2;
+    o2 += round_up(rows * sizeof(float));
+    L.lvec = o2;
+    o2 += round_up(rows * sizeof(float));
+    L.part_dq = o2;
+    o2 += round_up(slots * bb::kBlk * bb::kDim * sizeof(float));
+    L.part_dk = o2;
+    o2 += round_up(kv_slots * bb::kBlk * bb::kDim * sizeof(float));
+    L.part_dv = o2;
+    o2 += round_up(kv_slots * bb::kBlk * bb::kDim * sizeof(float));
+    L.bwd_total = o2;
+    if (o2 > L.total) L.total = o2;
+  }
   return L;
 }
 
@@ -78,8 +101,8 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
                              reinterpret_cast<uintptr_t>(key_padding_mask);
   if (align_or & 15) return BB_ERR_SHAPE;
   const WorkspaceLayout L = make_layout(B, H, n, b, g, w, r, 0);
-  if (L.total > 0) {
-    if (!workspace || workspace_bytes < L.total ||
+  if (L.fwd_total > 0) {
+    if (!workspace || workspace_bytes < L.fwd_total ||
         (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
       return BB_ERR_WORKSPACE;
   }
@@ -103,10 +126,42 @@ extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, con
                                 int H, int n, int d, int b, int g, int w, int r, float scale,
                                 int dtype, int global_mode, void* workspace,
                                 size_t workspace_bytes, void* hip_stream) {
-  (void)Q; (void)K; (void)V; (void)O; (void)LSE; (void)dO; (void)dQ; (void)dK; (void)dV;
-  (void)rand_idx; (void)key_padding_mask; (void)scale; (void)dtype; (void)workspace;
-  (void)workspace_bytes; (void)hip_stream;
   int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
-  return BB_ERR_UNSUPPORTED;
+  if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
+  if (!(scale > 0.f) || !std::isfinite(scale)) return BB_ERR_UNSUPPORTED;
+  if (dtype == BB_F32) return BB_ERR_UNSUPPORTED;  // the fp32 backward is not built
+  if (n / b > bb::kMaxBwdBlocks) return BB_ERR_UNSUPPORTED;
+  if (B == 0 || H == 0) return BB_OK;
+  if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return BB_ERR_NULL;
+  if (r > 0 && !rand_idx) return BB_ERR_NULL;
+  const uintptr_t align_or =
+      reinterpret_cast<uintptr_t>(Q) | reinterpret_cast<uintptr_t>(K) | reinterpret_cast<uintptr_t>(V) |
+      reinterpret_cast<uintptr_t>(O) | reinterpret_cast<uintptr_t>(dO) | reinterpret_cast<uintptr_t>(dQ) |
+      reinterpret_cast<uintptr_t>(dK) | reinterpret_cast<uintptr_t>(dV) |
+      reinterpret_cast<uintptr_t>(key_padding_mask);
+  if (align_or & 15) return BB_ERR_SHAPE;
+  const WorkspaceLayout L = make_layout(B, H, n, b, g, w, r, 1);
+  if (!workspace || workspace_bytes < L.bwd_total ||
+      (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
+    return BB_ERR_WORKSPACE;
+  bb::BwdParams p;
+  p.Q = Q; p.K = K; p.V = V; p.O = O; p.dO = dO; p.LSE = LSE;
+  p.dQ = dQ; p.dK = dK; p.dV = dV;
+  p.rand_idx = rand_idx;
+  p.kmask = key_padding_mask;
+  char* ws = static_cast<char*>(workspace);
+  p.Dvec = reinterpret_cast<float*>(ws + L.dvec);
+  p.Lvec = reinterpret_cast<float*>(ws + L.lvec);
+  p.part_dq = reinterpret_cast<float*>(ws + L.part_dq);
+  p.part_dk = reinterpret_cast<float*>(ws + L.part_dk);
+  p.part_dv = reinterpret_cast<float*>(ws + L.part_dv);
+  p.B = B; p.H = H; p.BH = B * H; p.n = n; p.nb = n / b;
+  p.g = g; p.w = w; p.r = r; p.global_mode = global_mode;
+  p.c = scale * bb::kLog2e;
+  p.scale = scale;
+  p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
+  p.cq = (p.nb + bb::kChunk - 1) / bb::kChunk;
+  p.kv_items_per_bh = g * p.cq + (p.nb - g);
+  return bb::launch_bwd_bf16(p, static_cast<hipStream_t>(hip_stream));
 }

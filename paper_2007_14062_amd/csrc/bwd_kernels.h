@@ -1,0 +1,40 @@
+// Launch interface of the backward kernels (internal to the library).
+#ifndef BB_BWD_KERNELS_H_
+#define BB_BWD_KERNELS_H_
+
+#include "kernel_common.h"
+
+namespace bb {
+
+constexpr int kMaxBwdBlocks = 1024;  // longest query-block list a key block can have (LDS list)
+
+struct BwdParams {
+  const void* Q;
+  const void* K;
+  const void* V;
+  const void* O;
+  const void* dO;
+  const float* LSE;
+  float* dQ;
+  float* dK;
+  float* dV;
+  const int32_t* rand_idx;
+  const uint8_t* kmask;
+  float* Dvec;     // [B*H*n]  D_i = sum_c dO_ic O_ic
+  float* Lvec;     // [B*H*n]  LSE_i * log2(e); +inf for rows without a valid key
+  float* part_dq;  // [slots][64][64] partial dQ of split rows (slots as in the forward)
+  float* part_dk;  // [B*H*g*cq][64][64] partial dK of global key blocks
+  float* part_dv;  // same for dV
+  int B, H, BH, n, nb, g, w, r, global_mode;
+  float c;      // scale * log2(e)
+  float scale;
+  RowSplit split;  // query-row decomposition (dQ kernel), as in the forward
+  int cq;          // slices of the query-block list of a global key block: ceil(nb / 8)
+  int kv_items_per_bh;  // g*cq + (nb - g)
+};
+
+// Enqueues: row sums D, the dQ kernel, the dK/dV kernel and the fixed-order reductions.
+int launch_bwd_bf16(const BwdParams& p, hipStream_t stream);
+
+}  // namespace bb
+#endif  // BB_BWD_KERNELS_H_

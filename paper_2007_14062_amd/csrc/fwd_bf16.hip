@@ -11,6 +11,7 @@
 //     than 2^8, so the accumulator rescale is rare; row sums are taken from the
 //     bf16-rounded probabilities with the packed dot instruction.
 #include "fwd_epilogue.h"
+#include "tile_ops.h"
 
 #include <cstdio>
 #include <type_traits>
@@ -21,51 +22,11 @@ namespace {
 
 constexpr float kLazyLog2 = 8.f;  // rescale when a row maximum grows by more than 2^8
 
-// s_waitcnt immediate that waits for all but `n` vector-memory loads (gfx9 encoding:
-// vmcnt in bits 3:0 and 15:14, other counters left at their maxima).
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
-constexpr int kLgkmcnt0 = 15 | (3 << 14) | (7 << 4);  // wait for all LDS reads, nothing else
-
-// Enqueue this wave's half of a 64x64 bf16 tile: global -> LDS, 16 bytes per lane,
-// four instructions per wave.  Instruction ii of wave wv fills LDS rows
-// 8*(2*ii+wv) .. +8 linearly (the hardware places lane l at M0 + 16*l), so the XOR
-// swizzle is applied on the global side: the lane that lands on chunk position p of
-// row r fetches chunk p ^ (r & 7).  `voff` is that per-lane byte offset inside the
-// tile (fixed for the kernel), `gtile` the wave-uniform tile address, `lds` the
-// LDS byte address of this wave's first 1 KB slot.
-// Written as inline asm so that the compiler's wait-count bookkeeping does not see
-// these loads: it would otherwise drain them before every LDS read.  The waits
-// are placed by hand (loads return in order, so vmcnt(N) is exact).
-__device__ __forceinline__ void tile_load_async(const char* gtile, unsigned lds, unsigned voff) {
-#pragma unroll
-  for (int ii = 0; ii < 4; ++ii)
-    asm volatile(
-        "s_mov_b32 m0, %2\n\t"
-        "global_load_lds_dwordx4 %0, %1"
-        :
-        : "v"(voff + ii * 2048), "s"(gtile), "s"(lds + ii * 2048)
-        : "memory");  // M0 is written here; nothing else in this kernel reads M0
-}
-
-__device__ __forceinline__ unsigned lds_addr(const void* p) {
-  return static_cast<unsigned>(reinterpret_cast<uintptr_t>((BB_LDS const char*)(p)));
-}
-
 }  // namespace
 
 #ifndef BB_FWD_WAVES_PER_EU
 #define BB_FWD_WAVES_PER_EU 2
 #endif
-
-// Workgroup barrier without the memory fence of __syncthreads(): the fence would
-// drain the LDS-bound loads still in flight.  Ordering is kept by the explicit
-// counter waits next to each use; the empty asm stops compiler reordering.
-#define BB_BARRIER()                       \
-  do {                                     \
-    asm volatile("" ::: "memory");         \
-    __builtin_amdgcn_s_barrier();          \
-    asm volatile("" ::: "memory");         \
-  } while (0)
 
 // Schedule of one work item (key blocks k_0 .. k_{cnt-1}); K and V each have two
 // LDS buffers:

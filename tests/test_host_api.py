@@ -154,6 +154,37 @@ def test_attn_fwd_host_checks_fire_before_any_launch():
     assert call(H=0) == 0
 
 
+def test_attn_bwd_host_checks_fire_before_any_launch():
+    lib = load_library()
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+
+    def call(Q=fake, K=fake, V=fake, O=fake, LSE=fake, dO=fake, dQ=fake, dK=fake, dV=fake, rand=fake,
+             km=None, B=1, H=2, n=1024, d=64, b=64, g=2, w=3, r=3, scale=0.125, dtype=1, mode=0,
+             ws=fake, ws_bytes=1 << 30):
+        return lib.bigbird_attn_bwd(Q, K, V, O, LSE, dO, dQ, dK, dV, rand, km, B, H, n, d, b, g, w, r,
+                                    scale, dtype, mode, ws, ws_bytes, None)
+
+    assert call(dO=None) == -1
+    assert call(dV=None) == -1
+    assert call(rand=None) == -1
+    assert call(n=1000) == -2
+    assert call(w=2) == -2
+    assert call(dK=odd) == -2
+    assert call(d=32) == -6
+    assert call(dtype=0) == -6                     # fp32 backward is not built: refused, not faked
+    assert call(dtype=9) == -4
+    assert call(scale=-1.0) == -6
+    assert call(n=64 * 2048) == -6                 # more key blocks than the backward's list holds
+    assert call(ws=None) == -5
+    assert call(ws_bytes=1024) == -5
+    assert call(B=0) == 0
+    need_fwd = bb.bigbird_attn_workspace_bytes(1, 2, 1024, 64, 64, 2, 3, 3, False)
+    need_bwd = bb.bigbird_attn_workspace_bytes(1, 2, 1024, 64, 64, 2, 3, 3, True)
+    assert need_bwd > need_fwd
+    assert call(ws_bytes=need_fwd) == -5           # a forward-sized workspace is too small
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     Q = torch.zeros(1, 1, 64, 64)
