@@ -97,7 +97,7 @@ void bwd_dq_kernel(BwdParams p) {
   const size_t qrow = bh_row0 + it.j * kBlk + wv * 32 + col;
   const char* kbase = static_cast<const char*>(p.K) + bh_row0 * (kDim * 2);
   const char* vbase = static_cast<const char*>(p.V) + bh_row0 * (kDim * 2);
-  const unsigned voff = ((wv * 8 + (lane >> 3)) * 128) + ((((lane & 7) ^ (lane >> 3))) << 4);
+  const unsigned voff = tile_load_lane_offset(wv, lane);
   const unsigned lds_k_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_k) + wv * 1024);
   const unsigned lds_v_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_v) + wv * 1024);
   auto tile_off = [&](int i) { return static_cast<size_t>(key_block(i)) * kTile; };
@@ -313,7 +313,7 @@ void bwd_dkv_kernel(BwdParams p) {
   const char* dobase = static_cast<const char*>(p.dO) + bh_row0 * (kDim * 2);
   const float* lbase = p.Lvec + bh_row0;
   const float* dbase = p.Dvec + bh_row0;
-  const unsigned voff = ((wv * 8 + (lane >> 3)) * 128) + ((((lane & 7) ^ (lane >> 3))) << 4);
+  const unsigned voff = tile_load_lane_offset(wv, lane);
   const unsigned lds_q_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_q) + wv * 1024);
   const unsigned lds_do_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_do) + wv * 1024);
   const unsigned lds_lse_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_lse));

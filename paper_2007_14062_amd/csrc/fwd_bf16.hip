@@ -22,6 +22,13 @@ namespace {
 
 constexpr float kLazyLog2 = 8.f;  // rescale when a row maximum grows by more than 2^8
 
+__device__ __forceinline__ void zero_acc(f32x16 (&a)[2]) {
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[t][r] = 0.f;
+}
+
 }  // namespace
 
 #ifndef BB_FWD_WAVES_PER_EU
@@ -64,7 +71,7 @@ void fwd_kernel_bf16(FwdParams p) {
   const char* vbase = static_cast<const char*>(p.V) + bh_row0 * (kDim * 2);
 
   // per-lane pieces of the tile loads (see tile_load_async)
-  const unsigned voff = ((wv * 8 + (lane >> 3)) * 128) + ((((lane & 7) ^ (lane >> 3))) << 4);
+  const unsigned voff = tile_load_lane_offset(wv, lane);
   const unsigned lds_k_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_k) + wv * 1024);
   const unsigned lds_v_wave = __builtin_amdgcn_readfirstlane(lds_addr(lds_v) + wv * 1024);
   auto tile_off = [&](int i) { return static_cast<size_t>(key_block(i)) * kTile; };
@@ -97,37 +104,8 @@ void fwd_kernel_bf16(FwdParams p) {
   const float c = p.c;
   const float tau = kLazyLog2 / c;
 
-  // LDS byte offsets of this lane's operand pieces (fixed for the whole item)
-  int koff[2][4];
-#pragma unroll
-  for (int t = 0; t < 2; ++t)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) koff[t][ks] = tile_off_bf16(t * 32 + col, ks * 2 + hf);
-  const int gq = lane >> 4, li = lane & 15;
-  int voff_tr[2];  // V^T operand: row (4*hf + li/4) of a 16-key group, 8-byte piece of a d chunk
-#pragma unroll
-  for (int dt = 0; dt < 2; ++dt)
-    voff_tr[dt] = tile_off_bf16(hf * 4 + (li >> 2), dt * 4 + (gq & 1) * 2 + ((li & 3) >> 1)) + (li & 1) * 8;
-
-  // S^T = K Q^T for the tile in K buffer `buf`: rows = 64 keys (two MFMA tiles), columns =
-  // this wave's 32 queries.
-  auto scores = [&](int buf, f32x16 (&s)[2]) {
-    const char* kt = lds_k + buf * kTile;
-    bf16x8 ka[2][4];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) ka[t][ks] = *reinterpret_cast<const bf16x8*>(kt + koff[t][ks]);
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], s[t], 0, 0, 0);
-  };
+  const StraightOffsets so(lane);
+  const TransposedOffsets to(lane);
 
   f32x16 sc[2][2];  // scores of the current and of the next key block
   if (cnt > 0) {
@@ -137,23 +115,50 @@ void fwd_kernel_bf16(FwdParams p) {
     else
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
     BB_BARRIER();
-    scores(0, sc[0]);
+    bf16x8 ka[2][4];
+    so.read(lds_k, ka);
+    zero_acc(sc[0]);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        sc[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], sc[0][t], 0, 0, 0);
   }
 
-  auto step = [&](auto parity, int i) {
+  // One key block.  P = parity of i (which buffers), MORE = a block i+1 exists.
+  // The instruction stream is laid out so that about one MFMA is issued per ten
+  // vector instructions: the eight MFMAs of the next block's scores and the eight of
+  // this block's value product are spread over the row-maximum and the four
+  // exponential groups (the vector ALU is the longer pipe at d = 64).
+  auto step = [&](auto parity, auto more_tag, int i) {
     constexpr int P = decltype(parity)::value;
+    constexpr bool MORE = decltype(more_tag)::value;
     f32x16(&s)[2] = sc[P];
-    const int kb = key_block(i);
+    f32x16(&sn)[2] = sc[P ^ 1];
     uint64_t vbits = ~0ull;
-    if (p.kmask) vbits = key_valid_bits(p.kmask, bi, p.n, kb);
+    if (p.kmask) vbits = key_valid_bits(p.kmask, bi, p.n, key_block(i));
+
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));  // K(i+1) and V(i) have landed
     __builtin_amdgcn_s_waitcnt(kLgkmcnt0);     // and this wave's reads of the buffers reused below are done
     BB_BARRIER();
-    if (i + 2 < cnt) tile_load_async(kbase + tile_off(i + 2), lds_k_wave + P * kTile, voff);
-    if (i + 1 < cnt) {
+    if constexpr (MORE) {
+      if (i + 2 < cnt) tile_load_async(kbase + tile_off(i + 2), lds_k_wave + P * kTile, voff);
       tile_load_async(vbase + tile_off(i + 1), lds_v_wave + (P ^ 1) * kTile, voff);
-      scores(P ^ 1, sc[P ^ 1]);  // next block's scores: runs on the MFMA pipe under the softmax below
     }
+    // all LDS operand reads of this step, up front: K(i+1) for the next scores, V(i)^T for
+    // this block's value product (see TransposedOffsets for the key order)
+    bf16x8 ka[2][4], va[2][4];
+    if constexpr (MORE) {
+      so.read(lds_k + (P ^ 1) * kTile, ka);
+      zero_acc(sn);
+    }
+    to.read(lds_v + P * kTile, va);
+    auto next_scores = [&](int idx) {  // MFMA idx (0..7) of S(i+1) = K(i+1) Q^T
+      if constexpr (MORE) {
+        const int ks = idx >> 1, t = idx & 1;
+        sn[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], sn[t], 0, 0, 0);
+      }
+    };
 
     if (vbits != ~0ull) {  // partly padded block: masked keys get -inf
       const uint64_t mine = vbits >> (hf * 4);
@@ -164,13 +169,18 @@ void fwd_kernel_bf16(FwdParams p) {
           if (!((mine >> (t * 32 + acc_row(r, 0))) & 1)) s[t][r] = neg_inf();
     }
 
-    // ---- online softmax, base 2, lazily moved reference
+    // ---- row maximum (base-2 online softmax with a lazily moved reference)
+    next_scores(0);
+    next_scores(1);
     float mloc = neg_inf();
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[0][r]);
+    next_scores(2);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[t][r]);
+    for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, s[1][r]);
+    next_scores(3);
     mloc = half_max(mloc);
+    __builtin_amdgcn_sched_barrier(0);
     if (__any(mloc > m_ref + tau)) {
       const float m_new = fmaxf(m_ref, mloc);
       const float m_use = (m_new == neg_inf()) ? 0.f : m_new;
@@ -184,22 +194,7 @@ void fwd_kernel_bf16(FwdParams p) {
     }
     const float mc = (m_ref == neg_inf()) ? 0.f : m_ref * c;
 
-    // V^T operand (A of O^T += V^T P^T): lane holds d = 32*dt + col and, in MFMA
-    // contraction slot 8*hf + kk, the key 16*sg + 4*hf + kk (kk < 4) or + 8 + kk - 4.
-    const char* vt = lds_v + P * kTile;
-    bf16x8 va[2][4];
-#pragma unroll
-    for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-      for (int sg = 0; sg < 4; ++sg) {
-        // rows 16*sg + {0, 8} + (4*hf + li/4): a multiple of 8 added to the row keeps the swizzle
-        const s16x4 lo = lds_read_tr16(vt + voff_tr[dt] + sg * 2048);
-        const s16x4 hi = lds_read_tr16(vt + voff_tr[dt] + sg * 2048 + 1024);
-        union { struct { s16x4 a, b; } h2; bf16x8 v; } u;
-        u.h2.a = lo;
-        u.h2.b = hi;
-        va[dt][sg] = u.v;
-      }
+    // ---- four groups of 16 keys: exponentials, then the group's share of O^T += V^T P^T
     const bf16x2 ones = {static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)};
 #pragma unroll
     for (int sg = 0; sg < 4; ++sg) {
@@ -213,17 +208,34 @@ void fwd_kernel_bf16(FwdParams p) {
         pb[kk] = pk[0];
         pb[kk + 1] = pk[1];
         l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
+        if (sg < 2 && kk == 2) next_scores(4 + 2 * sg);
+        if (sg < 2 && kk == 6) next_scores(5 + 2 * sg);
       }
 #pragma unroll
       for (int dt = 0; dt < 2; ++dt)
         o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pb, o[dt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
 
-  for (int i = 0; i < cnt; i += 2) {
-    step(std::integral_constant<int, 0>{}, i);
-    if (i + 1 < cnt) step(std::integral_constant<int, 1>{}, i + 1);
+  {
+    using T = std::true_type;
+    using F = std::false_type;
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    int i = 0;
+    for (; i + 2 < cnt; i += 2) {
+      step(P0{}, T{}, i);
+      step(P1{}, T{}, i + 1);
+    }
+    if (cnt - i == 2) {
+      step(P0{}, T{}, i);
+      step(P1{}, F{}, i + 1);
+    } else if (cnt - i == 1) {
+      step(P0{}, F{}, i);
+    }
   }
+
   const float l_tot = half_sum(l_run);
   fwd_store<true>(p, it, o, m_ref, l_tot, c, qrow, wv * 32 + col, hf);
 }

@@ -57,10 +57,25 @@ __device__ __forceinline__ int mask_rank(uint64_t m) {
 // sits in row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 __device__ __forceinline__ constexpr int acc_row(int r, int hf) { return 8 * (r >> 2) + 4 * hf + (r & 3); }
 
-// Byte offset of 16-byte chunk c of row `row` in a 64x64 bf16 tile kept in LDS
-// with 128-byte rows; the chunk index is XOR-swizzled with the row to spread banks.
+// Bank swizzle of a 64x64 bf16 tile kept in LDS with 128-byte rows: 16-byte chunk c of
+// row `row` is stored at chunk position c ^ tile_swizzle(row).  LDS has 64 four-byte
+// banks, so the row parity already selects a bank half and the swizzle uses row bits
+// 1..3: bit 1 goes to position bit 2 (two rows of equal parity read by one transposing
+// load then use different 64-byte halves), bits 2..3 to position bits 0..1 (the eight
+// equal-parity rows read by one 16-lane pass of a 128-bit load get eight positions).
+__device__ __forceinline__ int tile_swizzle(int row) { return (((row >> 1) & 1) << 2) | ((row >> 2) & 3); }
+
+// Byte offset of 16-byte chunk c of row `row` in such a tile.
 __device__ __forceinline__ int tile_off_bf16(int row, int chunk) {
-  return row * 128 + ((chunk ^ (row & 7)) << 4);
+  return row * 128 + ((chunk ^ tile_swizzle(row)) << 4);
+}
+
+// Per-lane byte offset inside a tile for the asynchronous tile loads: instruction ii of
+// wave wv fills rows 16*ii + 8*wv .. +8 linearly, lane l landing on row l/8, chunk
+// position l%8, so it must fetch the chunk that the swizzle stores there.
+__device__ __forceinline__ unsigned tile_load_lane_offset(int wv, int lane) {
+  const int row = wv * 8 + (lane >> 3);  // + 16*ii: bits 1..3 of the row do not depend on ii
+  return row * 128 + (((lane & 7) ^ tile_swizzle(row)) << 4);
 }
 
 // ds_read_b64_tr_b16: inside each group of 16 lanes, lane i passes the address of

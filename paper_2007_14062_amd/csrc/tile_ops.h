@@ -15,9 +15,9 @@ constexpr int kLgkmcnt0 = 15 | (3 << 14) | (7 << 4);  // wait for all LDS reads,
 // four instructions per wave.  Instruction ii of wave wv fills LDS rows
 // 8*(2*ii+wv) .. +8 linearly (the hardware places lane l at M0 + 16*l), so the XOR
 // swizzle is applied on the global side: the lane that lands on chunk position p of
-// row r fetches chunk p ^ (r & 7).  `voff` is that per-lane byte offset inside the
-// tile (fixed for the kernel), `gtile` the wave-uniform tile address, `lds` the
-// LDS byte address of this wave's first 1 KB slot.
+// row r fetches chunk p ^ tile_swizzle(r).  `voff` is that per-lane byte offset inside
+// the tile (tile_load_lane_offset, fixed for the kernel), `gtile` the wave-uniform tile
+// address, `lds` the LDS byte address of this wave's first 1 KB slot.
 // Written as inline asm so that the compiler's wait-count bookkeeping does not see
 // these loads: it would otherwise drain them before every LDS read.  The waits
 // are placed by hand (loads return in order, so vmcnt(N) is exact).
@@ -76,17 +76,20 @@ struct StraightOffsets {
 // ds_read_b64_tr_b16.  Used for V^T in O^T += V^T P^T, K^T in dQ^T += K^T dS^T, dO^T and
 // Q^T in the key-major backward kernel.
 struct TransposedOffsets {
-  int off[2];  // byte offsets for dt = 0, 1 (sg adds 2048, the second half 1024)
+  int off[2][2];  // byte offsets for dt = 0, 1 and the two 4-row pieces (sg adds 2048)
   __device__ __forceinline__ explicit TransposedOffsets(int lane) {
     const int hf = lane >> 5, gq = lane >> 4, li = lane & 15;
 #pragma unroll
     for (int dt = 0; dt < 2; ++dt)
-      off[dt] = tile_off_bf16(hf * 4 + (li >> 2), dt * 4 + (gq & 1) * 2 + ((li & 3) >> 1)) + (li & 1) * 8;
+#pragma unroll
+      for (int half = 0; half < 2; ++half)
+        off[dt][half] = tile_off_bf16(half * 8 + hf * 4 + (li >> 2), dt * 4 + (gq & 1) * 2 + ((li & 3) >> 1)) +
+                        (li & 1) * 8;
   }
   __device__ __forceinline__ bf16x8 read_one(const char* tile, int dt, int sg) const {
-    // rows 16*sg + {0, 8} + (4*hf + li/4): adding a multiple of 8 rows keeps the swizzle
-    const s16x4 lo = lds_read_tr16(tile + off[dt] + sg * 2048);
-    const s16x4 hi = lds_read_tr16(tile + off[dt] + sg * 2048 + 1024);
+    // rows 16*sg + {0, 8} + (4*hf + li/4): adding a multiple of 16 rows keeps the swizzle
+    const s16x4 lo = lds_read_tr16(tile + off[dt][0] + sg * 2048);
+    const s16x4 hi = lds_read_tr16(tile + off[dt][1] + sg * 2048);
     union { struct { s16x4 a, b; } h2; bf16x8 v; } u;
     u.h2.a = lo;
     u.h2.b = hi;
