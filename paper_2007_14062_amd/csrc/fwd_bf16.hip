@@ -59,9 +59,10 @@ __device__ __forceinline__ void tile_load_async_wave(const char* gtile, unsigned
 
 __global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void fwd_kernel_bf16(FwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds_k[kTile];
-  __shared__ __attribute__((aligned(1024))) char lds_v[kTile];
+  __shared__ __attribute__((aligned(1024))) char lds_kv[2 * kTile];  // K tile, then V tile
   __shared__ int klist[kChunk];
+  char* const lds_k = lds_kv;
+  char* const lds_v = lds_kv + kTile;
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   WorkItem it;
@@ -225,10 +226,68 @@ void fwd_kernel_bf16(FwdParams p) {
     }
   }
 
+  // ---- finalise.  The accumulators hold O^T (a lane owns one query and scattered groups
+  // of four d); they are turned through LDS (free now) so that global memory sees whole
+  // rows: 16 bytes per lane, consecutive lanes on consecutive addresses.
+  float l_tot[2];
 #pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const float l_tot = half_sum(l_run[q]);
-    fwd_store<true>(p, it, o[q], m_ref[q], l_tot, c, qrow0 + q * 32, q * 32 + col, hf);
+  for (int q = 0; q < 2; ++q) l_tot[q] = half_sum(l_run[q]);
+  const size_t row_blk = bh_row0 + it.j * kBlk;  // first row of the query block
+  if (it.nchunks == 1) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const float inv = l_tot[q] > 0.f ? 1.f / l_tot[q] : 0.f;
+      if (hf == 0)
+        p.LSE[qrow0 + q * 32] = l_tot[q] > 0.f ? (m_ref[q] * c + fast_log2(l_tot[q])) * kLn2 : neg_inf();
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          bf16x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(o[q][dt][r4 * 4 + e] * inv);
+          // d0 = 32 dt + 8 r4 + 4 hf: 16-byte chunk 4 dt + r4, upper or lower half of it
+          *reinterpret_cast<bf16x4*>(lds_kv + tile_off_bf16(q * 32 + col, dt * 4 + r4) + hf * 8) = v;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+    asm volatile("" ::: "memory");
+    __bf16* orow = static_cast<__bf16*>(p.O) + row_blk * kDim;
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      const int row = ii * 8 + (lane >> 3), chunk = lane & 7;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(lds_kv + tile_off_bf16(row, chunk));
+      *reinterpret_cast<u32x4*>(orow + row * kDim + chunk * 8) = v;
+    }
+  } else {
+    // partial (m, l, un-normalised O) of a split row, fp32: d 0..31 in the first 8 KB, d 32..63
+    // in the second, each laid out like a bf16 tile (128-byte rows of 32 floats)
+    float* pml = p.part_ml + static_cast<size_t>(it.slot) * (2 * kBlk);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      if (hf == 0) {
+        pml[q * 32 + col] = (m_ref[q] == neg_inf()) ? neg_inf() : m_ref[q] * c;
+        pml[kBlk + q * 32 + col] = l_tot[q];
+      }
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+          f32x4 v;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = o[q][dt][r4 * 4 + e];
+          *reinterpret_cast<f32x4*>(lds_kv + dt * kTile + tile_off_bf16(q * 32 + col, r4 * 2 + hf)) = v;
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+    asm volatile("" ::: "memory");
+    float* po = p.part_o + static_cast<size_t>(it.slot) * (kBlk * kDim);
+#pragma unroll
+    for (int ii = 0; ii < 16; ++ii) {
+      const int row = ii * 4 + (lane >> 4), cc = lane & 15;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(lds_kv + (cc >> 3) * kTile + tile_off_bf16(row, cc & 7));
+      *reinterpret_cast<f32x4*>(po + row * kDim + cc * 4) = v;
+    }
   }
 }
 
