@@ -77,6 +77,48 @@ def time_cpu_oracle(wl, t, rand_idx, sample_heads: int):
     }
 
 
+def time_fwd_bwd(bb, torch, dev, steps: int, warmup: int):
+    """Forward + backward on the cfg4 workload (B=2): ms per step and useful TFLOP/s.
+
+    Useful flops: 4 b^2 d per block pair forward, 10 b^2 d backward (five matmuls); the two
+    backward kernels recompute the scores, so 14 b^2 d are executed.
+    """
+    wl = inp.WORKLOADS["cfg4_fwd_bwd"]
+    rand_idx = bb.bigbird_make_rand_idx(wl.H, wl.n, wl.b, wl.g, wl.w, wl.r, wl.pattern_seed)
+    _, dv = device_inputs(wl, torch, dev)
+    ridx = torch.from_numpy(rand_idx).to(dev)
+    pairs = bb.bigbird_count_block_pairs(rand_idx, None, wl.B, wl.H, wl.n, wl.b, wl.g, wl.w, wl.r)
+    O = torch.empty_like(dv["Q"])
+    LSE = torch.empty((wl.B, wl.H, wl.n), dtype=torch.float32, device=dev)
+    grads = [torch.empty(dv["Q"].shape, dtype=torch.float32, device=dev) for _ in range(3)]
+    ws = torch.empty(bb.bigbird_attn_workspace_bytes(wl.B, wl.H, wl.n, wl.d, wl.b, wl.g, wl.w, wl.r, True),
+                     dtype=torch.uint8, device=dev)
+    fwd = bb.prepare_attn_fwd(dv["Q"], dv["K"], dv["V"], ridx, O, LSE, ws, g=wl.g, w=wl.w, scale=wl.scale)
+    bwd = bb.prepare_attn_bwd(dv["Q"], dv["K"], dv["V"], O, LSE, dv["dO"], ridx, *grads, ws,
+                              g=wl.g, w=wl.w, scale=wl.scale)
+    out = {}
+    for name, fns, mult in (("forward", (fwd,), 4.0), ("backward", (bwd,), 10.0),
+                            ("forward_backward", (fwd, bwd), 14.0)):
+        for _ in range(warmup):
+            for f in fns:
+                f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            for f in fns:
+                f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        fl = mult * wl.b * wl.b * wl.d * pairs
+        out[name] = {"ms_per_step": ms, "useful_tflops": fl / (ms * 1e-3) / 1e12,
+                     "pct_of_bf16_mfma_peak": 100.0 * fl / (ms * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+    out["workload"] = wl.name
+    out["block_pairs"] = pairs
+    return out
+
+
 def measured_traffic_bytes():
     """HBM bytes per forward call from the committed rocprofv3 counter summary (None if absent)."""
     path = os.path.join(ROOT, "profiles", "fwd_kernel_bf16_cfg2_hbm_traffic.md")
@@ -96,6 +138,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=500)
     ap.add_argument("--cpu-sample-heads", type=int, default=12)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-backward", action="store_true",
+                    help="leave out the forward+backward timing on the cfg4 workload (extra fields only)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 256 MiB device copy 10 times (known HBM traffic: 256 MiB read, "
                          "256 MiB written per copy), to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters")
@@ -175,6 +219,8 @@ def main():
                      "traffic": measured_traffic_bytes(),
                      "kernel": "fwd_kernel<bf16> (+ fwd_combine_kernel, same timed region)"},
     }
+    if not args.skip_backward:
+        result["fwd_bwd_cfg4"] = time_fwd_bwd(bb, torch, dev, max(1, args.steps // 4), max(1, args.warmup // 4))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = time_cpu_oracle(wl, t, rand_idx, args.cpu_sample_heads)
     print(json.dumps(result))

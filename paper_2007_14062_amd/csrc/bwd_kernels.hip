@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void bwd_dq_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTile];
   __shared__ __attribute__((aligned(1024))) char lds_v[2 * kTile];
-  __shared__ int klist[kChunk];
+  __shared__ int klist[kChunkMax];
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   WorkItem it;
@@ -90,7 +90,7 @@ void bwd_dq_kernel(BwdParams p) {
   const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
                                  it.chunk, klist);
   __syncthreads();
-  const int kl = klist[lane & (kChunk - 1)];
+  const int kl = klist[lane & (kChunkMax - 1)];
   auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
 
   const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
@@ -435,16 +435,17 @@ void bwd_dkv_kernel(BwdParams p) {
 // ---------------------------------------------------------------------------------------
 // Fixed-order sums of the partial gradients of split rows (dQ) and split columns (dK, dV)
 // ---------------------------------------------------------------------------------------
-// mode 0: dQ blocks of split query rows; mode 1: dK (blockIdx.y = 0) and dV (1) of global keys.
-// Four workgroups per 64x64 block, thread t owns 4 columns of row part*16 + t/16.
-__global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdParams p, int mode) {
+// One launch covers all three: blocks [0, nq) are the dQ blocks of split query rows, then
+// come the dK and the dV blocks of the global key blocks.  Four workgroups per 64x64 block,
+// thread t owns 4 columns of row part*16 + t/16.
+__global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdParams p, int nq_blocks, int nkv_blocks) {
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   const int part = blockIdx.x & 3;
-  const int blk = blockIdx.x >> 2;
+  int blk = blockIdx.x >> 2;
   const float* src;
   float* dst;
   int nslices;
-  if (mode == 0) {
+  if (blk < nq_blocks) {
     const RowSplit& s = p.split;
     const int nglob_rows = s.cg > 1 ? p.g : 0;
     const int nsparse_rows = s.cs > 1 ? p.nb - p.g : 0;
@@ -464,11 +465,14 @@ __global__ __launch_bounds__(256) void bwd_reduce_kernel(BwdParams p, int mode) 
     src = p.part_dq + static_cast<size_t>(slot0) * (kBlk * kDim);
     dst = p.dQ + (static_cast<size_t>(bh) * p.n + j * kBlk) * kDim;
   } else {
+    blk -= nq_blocks;
+    const bool is_dv = blk >= nkv_blocks;
+    if (is_dv) blk -= nkv_blocks;
     const int bh = blk / p.g, gi = blk % p.g;
     nslices = p.cq;
     const size_t slot0 = static_cast<size_t>(bh * p.g + gi) * p.cq;
-    src = (blockIdx.y == 0 ? p.part_dk : p.part_dv) + slot0 * (kBlk * kDim);
-    dst = (blockIdx.y == 0 ? p.dK : p.dV) + (static_cast<size_t>(bh) * p.n + pat.global_block(gi) * kBlk) * kDim;
+    src = (is_dv ? p.part_dv : p.part_dk) + slot0 * (kBlk * kDim);
+    dst = (is_dv ? p.dV : p.dK) + (static_cast<size_t>(bh) * p.n + pat.global_block(gi) * kBlk) * kDim;
   }
   const int off = (part * 16 + (threadIdx.x >> 4)) * kDim + (threadIdx.x & 15) * 4;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -509,20 +513,19 @@ int launch_bwd_bf16(const BwdParams& p, hipStream_t stream) {
   const unsigned qgrid = static_cast<unsigned>(kXcd) * s.bh_rounds * s.items_per_bh;
   hipLaunchKernelGGL(bwd_dq_kernel, dim3(qgrid), dim3(kThreads), 0, stream, p);
   if (launch_failed("bwd_dq_kernel")) return BB_ERR_LAUNCH;
-  const int rows_per_bh = (s.cg > 1 ? p.g : 0) + (s.cs > 1 ? p.nb - p.g : 0);
-  if (rows_per_bh > 0) {
-    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(static_cast<unsigned>(p.BH) * rows_per_bh * 4), dim3(256), 0,
-                       stream, p, 0);
-    if (launch_failed("bwd_reduce_kernel(dQ)")) return BB_ERR_LAUNCH;
-  }
-
   const unsigned kvgrid = static_cast<unsigned>(kXcd) * s.bh_rounds * p.kv_items_per_bh;
   hipLaunchKernelGGL(bwd_dkv_kernel, dim3(kvgrid), dim3(kThreads), 0, stream, p);
   if (launch_failed("bwd_dkv_kernel")) return BB_ERR_LAUNCH;
-  if (p.g > 0 && p.cq > 1) {
-    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(static_cast<unsigned>(p.BH) * p.g * 4, 2), dim3(256), 0, stream,
-                       p, 1);
-    if (launch_failed("bwd_reduce_kernel(dK,dV)")) return BB_ERR_LAUNCH;
+
+  // one reduction launch for the split dQ rows and the split dK / dV columns
+  const int rows_per_bh = (s.cg > 1 ? p.g : 0) + (s.cs > 1 ? p.nb - p.g : 0);
+  const int nq_blocks = p.BH * rows_per_bh;
+  const int nkv_blocks = (p.g > 0 && p.cq > 1) ? p.BH * p.g : 0;
+  const int total = nq_blocks + 2 * nkv_blocks;
+  if (total > 0) {
+    hipLaunchKernelGGL(bwd_reduce_kernel, dim3(static_cast<unsigned>(total) * 4), dim3(256), 0, stream, p,
+                       nq_blocks, nkv_blocks);
+    if (launch_failed("bwd_reduce_kernel")) return BB_ERR_LAUNCH;
   }
   return BB_OK;
 }

@@ -60,7 +60,7 @@ __device__ __forceinline__ void tile_load_async_wave(const char* gtile, unsigned
 __global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void fwd_kernel_bf16(FwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds_kv[2 * kTile];  // K tile, then V tile
-  __shared__ int klist[kChunk];
+  __shared__ int klist[kChunkMax];
   char* const lds_k = lds_kv;
   char* const lds_v = lds_kv + kTile;
 
@@ -74,7 +74,7 @@ void fwd_kernel_bf16(FwdParams p) {
   const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
                                  it.chunk, klist);
   __syncthreads();  // one wave: only orders the LDS write above against the read below
-  const int kl = klist[lane & (kChunk - 1)];  // lane t holds list entry t & 7
+  const int kl = klist[lane & (kChunkMax - 1)];  // lane t holds list entry t % kChunkMax
   auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
 
   const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;

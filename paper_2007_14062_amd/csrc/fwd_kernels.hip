@@ -49,7 +49,7 @@ __device__ __forceinline__ void tile_store_f32(char* lds, const u32x4* regs) {
 __global__ __launch_bounds__(kThreads) void fwd_kernel_f32(FwdParams p) {
   __shared__ __attribute__((aligned(16))) char lds_k[kTileBytesF32];
   __shared__ __attribute__((aligned(16))) char lds_v[kTileBytesF32];
-  __shared__ int klist[kChunk];
+  __shared__ int klist[kChunkMax];
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   WorkItem it;

@@ -11,7 +11,12 @@ namespace bb {
 
 constexpr int kBlk = 64;      // block length b (App. E.1: 64 for every ITC model)
 constexpr int kDim = 64;      // head width d
-constexpr int kChunk = 8;     // key blocks handled by one workgroup (= g+w+r of the ITC base pattern)
+constexpr int kChunk = 8;     // key blocks per work item of a non-global row (= g+w+r of the ITC base pattern)
+#ifndef BB_CHUNK_GLOBAL
+#define BB_CHUNK_GLOBAL 8
+#endif
+constexpr int kChunkGlobal = BB_CHUNK_GLOBAL;  // key blocks per work item of a global row (equal to kChunk: equal-length items balance best)
+constexpr int kChunkMax = kChunkGlobal > kChunk ? kChunkGlobal : kChunk;
 constexpr int kWaves = 2;     // one wave owns 32 query rows of the 64-row block
 constexpr int kThreads = 64 * kWaves;
 constexpr int kXcd = 8;       // accelerator dies; workgroup id modulo 8 selects the die
@@ -91,7 +96,8 @@ constexpr int kF32Stride = 68;  // floats per row of an fp32 tile in LDS (64 + 4
 struct WorkItem {
   int bh;       // batch * H + head
   int j;        // query block
-  int chunk;    // slice [chunk*kChunk, (chunk+1)*kChunk) of the row's key-block list
+  int chunk;    // slice number: entries [chunk*len, (chunk+1)*len) of the row's key-block list,
+                // len = kChunkGlobal for a global row, kChunk otherwise
   int nchunks;  // slices this row is split into
   int slot;     // partial-result slot (valid when nchunks > 1)
   bool row_global;
@@ -110,7 +116,7 @@ inline RowSplit make_row_split(int BH, int nb, int g, int w, int r) {
   RowSplit s;
   int sparse_ub = g + w + r;
   if (sparse_ub > nb) sparse_ub = nb;
-  s.cg = (nb + kChunk - 1) / kChunk;
+  s.cg = (nb + kChunkGlobal - 1) / kChunkGlobal;
   s.cs = (sparse_ub + kChunk - 1) / kChunk;
   if (s.cs < 1) s.cs = 1;
   s.items_per_bh = g * s.cg + (nb - g) * s.cs;
@@ -161,7 +167,7 @@ __device__ __forceinline__ bool block_has_valid_key(const uint8_t* kmask, int bi
 }
 
 // Key blocks attended by query block j of head h (App. D items 1-3 as a set
-// union, minus blocks without a valid key), slice [chunk*kChunk, +kChunk) of the
+// union, minus blocks without a valid key), slice `chunk` (see WorkItem) of the
 // ascending-by-candidate list.  Every lane of the calling wave takes part; the
 // slice is written to klist[0..count) and the count returned (wave uniform).
 // Candidate order: global blocks, window blocks, random blocks; a candidate is
@@ -172,7 +178,8 @@ __device__ __forceinline__ int build_key_list(const Pattern& pat, const int32_t*
   const int lane = lane_id();
   const int nb = pat.nb;
   const int ncand = row_global ? nb : pat.g + pat.w + r;
-  const int lo = chunk * kChunk, hi = lo + kChunk;
+  const int len = row_global ? kChunkGlobal : kChunk;
+  const int lo = chunk * len, hi = lo + len;
   const int32_t* rrow = rand_idx ? rand_idx + (static_cast<size_t>(h) * nb + j) * r : nullptr;
   int base = 0;
   for (int c0 = 0; c0 < ncand && base < hi; c0 += 64) {
@@ -203,7 +210,7 @@ __device__ __forceinline__ int build_key_list(const Pattern& pat, const int32_t*
     base += __popcll(m);
   }
   int cnt = base - lo;
-  cnt = cnt < 0 ? 0 : (cnt > kChunk ? kChunk : cnt);
+  cnt = cnt < 0 ? 0 : (cnt > len ? len : cnt);
   return cnt;
 }
 
