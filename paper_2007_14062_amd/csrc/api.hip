@@ -117,6 +117,28 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
   p.g = g; p.w = w; p.r = r; p.global_mode = global_mode;
   p.c = scale * bb::kLog2e;
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
+  if (dtype == BB_BF16) {
+    bb::Bf16Geom& q = p.geo;
+    q.ng = (p.nb + 4 * bb::kGlobalWaveLen - 1) / (4 * bb::kGlobalWaveLen);
+    q.cs = p.split.cs;
+    q.n_sitems = (p.nb - g) * q.cs;
+    q.s_wgs = (q.n_sitems + 3) / 4;
+    q.g_wgs = g * q.ng;
+    q.bh_rounds = p.split.bh_rounds;
+    p.cmb_g_rows = q.ng > 1 ? g : 0;
+    p.cmb_g_n = q.ng;
+    p.cmb_s_rows = q.cs > 1 ? p.nb - g : 0;
+    p.cmb_s_n = q.cs;
+  } else {
+    p.geo = bb::Bf16Geom{};
+    p.cmb_g_rows = p.split.cg > 1 ? g : 0;
+    p.cmb_g_n = p.split.cg;
+    p.cmb_s_rows = p.split.cs > 1 ? p.nb - g : 0;
+    p.cmb_s_n = p.split.cs;
+  }
+  // slot numbering: the global rows' slices first, then the non-global rows' (the workspace
+  // is sized for the fp32 decomposition, which never needs fewer slots)
+  p.slots_per_bh = p.cmb_g_rows * p.cmb_g_n + p.cmb_s_rows * p.cmb_s_n;
   return bb::launch_fwd(p, dtype == BB_BF16, static_cast<hipStream_t>(hip_stream));
 }
 

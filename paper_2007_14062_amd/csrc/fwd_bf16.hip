@@ -4,9 +4,12 @@
 // organised around what limits it on this chip at d = 64: the vector ALU (one
 // exponential per score) and the LDS read port (every MFMA wants a fresh 1 KB
 // operand), not the matrix pipe.
-//   * One wavefront owns one work item: a 64-query block against <= 8 key blocks.
-//     No workgroup barrier exists in the kernel; the two waves that share a SIMD
-//     belong to different items and fill each other's stalls.
+//   * One wavefront owns one work item: a 64-query block against a slice of its key
+//     blocks.  Waves never wait for each other inside the key-block loop.  A workgroup
+//     is four such waves: either four consecutive non-global query blocks (independent
+//     items), or one global query block whose key list is dealt out 16 blocks per wave
+//     and merged in LDS at the end (no partial results in HBM, no second kernel, for
+//     up to 64 key blocks; longer rows take several workgroups plus the merge kernel).
 //   * The wave's queries form two 32-column MFMA tiles (A, B).  Every K and V^T
 //     operand fetched from LDS feeds two MFMAs (one per tile), which halves the LDS
 //     traffic per flop, and the tiles ping-pong: while the vector ALU exponentiates
@@ -29,7 +32,8 @@ namespace bb {
 namespace {
 
 constexpr float kLazyLog2 = 8.f;  // rescale when a row maximum grows by more than 2^8
-constexpr int kFwdThreads = 64;   // one wavefront per work item
+constexpr int kFwdWaves = 4;
+constexpr int kFwdThreads = 64 * kFwdWaves;  // four independent wavefronts, one work item each
 constexpr int kTile = kBlk * kDim * 2;  // 8 KB
 
 __device__ __forceinline__ void zero_acc(f32x16 (&a)[2]) {
@@ -39,12 +43,20 @@ __device__ __forceinline__ void zero_acc(f32x16 (&a)[2]) {
     for (int r = 0; r < 16; ++r) a[t][r] = 0.f;
 }
 
+__device__ __forceinline__ const char* uniform_ptr(const char* p) {
+  const uintptr_t v = reinterpret_cast<uintptr_t>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(v));
+  const unsigned hi = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(v >> 32));
+  return reinterpret_cast<const char*>((static_cast<uintptr_t>(hi) << 32) | lo);
+}
+
 // A whole 64x64 bf16 tile, global -> LDS, by one wave: eight instructions of 64 lanes x
 // 16 bytes.  Instruction ii fills LDS rows 8*ii .. 8*ii+7 linearly (lane l lands on row
 // l/8, chunk position l%8) and fetches, for that place, the chunk the swizzle stores
 // there.  The swizzle depends on row bits 1..3, i.e. on l/8 and on the parity of ii:
 // voff[0] / voff[1] are the per-lane byte offsets for even / odd ii.
-__device__ __forceinline__ void tile_load_async_wave(const char* gtile, unsigned lds, const unsigned (&voff)[2]) {
+__device__ __forceinline__ void tile_load_async_wave(const char* gtile_, unsigned lds, const unsigned (&voff)[2]) {
+  const char* gtile = uniform_ptr(gtile_);  // wave-uniform by construction: keep it in scalar registers
 #pragma unroll
   for (int ii = 0; ii < 8; ++ii)
     asm volatile(
@@ -59,22 +71,61 @@ __device__ __forceinline__ void tile_load_async_wave(const char* gtile, unsigned
 
 __global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void fwd_kernel_bf16(FwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds_kv[2 * kTile];  // K tile, then V tile
-  __shared__ int klist[kChunkMax];
-  char* const lds_k = lds_kv;
-  char* const lds_v = lds_kv + kTile;
+  __shared__ __attribute__((aligned(1024))) char lds_all[kFwdWaves][2 * kTile];  // per wave: K tile, V tile
+  __shared__ int klist_all[kFwdWaves][kGlobalWaveLen];
+  __shared__ float mrg_m[kFwdWaves][kBlk], mrg_l[kFwdWaves][kBlk];  // global rows: per-wave exponent, sum
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
-  WorkItem it;
-  if (!decode_item(p.split, pat, p.BH, blockIdx.x, &it)) return;
-  const int bi = it.bh / p.H, h = it.bh % p.H;
-  const int lane = lane_id();
+  const Bf16Geom& geo = p.geo;
+  const int lane = lane_id(), wv = threadIdx.x >> 6;
   const int hf = lane >> 5, col = lane & 31;
+  char* const lds_kv = lds_all[wv];
+  char* const lds_k = lds_kv;
+  char* const lds_v = lds_kv + kTile;
+  int* const klist = klist_all[wv];
 
-  const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
-                                 it.chunk, klist);
-  __syncthreads();  // one wave: only orders the LDS write above against the read below
-  const int kl = klist[lane & (kChunkMax - 1)];  // lane t holds list entry t % kChunkMax
+  // Workgroup id -> work.  id % 8 is the die (XCD) the hardware dispatches to; each die gets
+  // whole (batch, head) slices so that a slice's K and V stay in its L2.  Within a die the
+  // global-row workgroups of all its slices come first: they are the longest.
+  WorkItem it;
+  int list_lo, list_len;
+  {
+    const int xcd = blockIdx.x % kXcd;
+    unsigned q = blockIdx.x / kXcd;
+    const unsigned n_gpart = static_cast<unsigned>(geo.bh_rounds) * geo.g_wgs;
+    if (q < n_gpart) {
+      it.bh = (q / geo.g_wgs) * kXcd + xcd;
+      const int gidx = q % geo.g_wgs;
+      const int row = gidx / geo.ng, u = gidx % geo.ng;
+      it.row_global = true;
+      it.j = pat.global_block(row);
+      it.chunk = u;
+      it.nchunks = geo.ng;
+      it.slot = it.bh * p.slots_per_bh + row * geo.ng + u;
+      list_lo = (u * kFwdWaves + wv) * kGlobalWaveLen;
+      list_len = kGlobalWaveLen;
+      if (it.bh >= p.BH) return;  // whole workgroup
+    } else {
+      q -= n_gpart;
+      it.bh = (q / geo.s_wgs) * kXcd + xcd;
+      const int sitem = (q % geo.s_wgs) * kFwdWaves + wv;
+      if (it.bh >= p.BH || sitem >= geo.n_sitems) return;  // no barrier follows for these workgroups
+      it.row_global = false;
+      it.j = pat.sparse_block(sitem / geo.cs);
+      it.chunk = sitem % geo.cs;
+      it.nchunks = geo.cs;
+      it.slot = it.bh * p.slots_per_bh + p.cmb_g_rows * p.cmb_g_n + sitem;
+      list_lo = it.chunk * kChunk;
+      list_len = kChunk;
+    }
+  }
+  const int bi = it.bh / p.H, h = it.bh % p.H;
+
+  const int cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
+                                       list_lo, list_len, klist);
+  // same wave wrote and reads the list: LDS keeps a wave's accesses in order, the compiler must too
+  asm volatile("" ::: "memory");
+  const int kl = klist[lane & (kGlobalWaveLen - 1)];  // lane t holds list entry t % 16
   auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
 
   const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
@@ -233,7 +284,7 @@ void fwd_kernel_bf16(FwdParams p) {
 #pragma unroll
   for (int q = 0; q < 2; ++q) l_tot[q] = half_sum(l_run[q]);
   const size_t row_blk = bh_row0 + it.j * kBlk;  // first row of the query block
-  if (it.nchunks == 1) {
+  if (!it.row_global && it.nchunks == 1) {
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const float inv = l_tot[q] > 0.f ? 1.f / l_tot[q] : 0.f;
@@ -259,26 +310,32 @@ void fwd_kernel_bf16(FwdParams p) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(lds_kv + tile_off_bf16(row, chunk));
       *reinterpret_cast<u32x4*>(orow + row * kDim + chunk * 8) = v;
     }
-  } else {
-    // partial (m, l, un-normalised O) of a split row, fp32: d 0..31 in the first 8 KB, d 32..63
-    // in the second, each laid out like a bf16 tile (128-byte rows of 32 floats)
+    return;
+  }
+
+  // Un-normalised O of this wave as an fp32 [64 q][64 d] tile in its LDS region: d 0..31 in the
+  // first 8 KB, d 32..63 in the second, each laid out like a bf16 tile (128-byte rows of 32 floats).
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = o[q][dt][r4 * 4 + e];
+        *reinterpret_cast<f32x4*>(lds_kv + dt * kTile + tile_off_bf16(q * 32 + col, r4 * 2 + hf)) = v;
+      }
+
+  if (!it.row_global) {
+    // slice of a non-global row with several slices: partial triple for the merge kernel
     float* pml = p.part_ml + static_cast<size_t>(it.slot) * (2 * kBlk);
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+    for (int q = 0; q < 2; ++q)
       if (hf == 0) {
         pml[q * 32 + col] = (m_ref[q] == neg_inf()) ? neg_inf() : m_ref[q] * c;
         pml[kBlk + q * 32 + col] = l_tot[q];
       }
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          f32x4 v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = o[q][dt][r4 * 4 + e];
-          *reinterpret_cast<f32x4*>(lds_kv + dt * kTile + tile_off_bf16(q * 32 + col, r4 * 2 + hf)) = v;
-        }
-    }
     __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
     asm volatile("" ::: "memory");
     float* po = p.part_o + static_cast<size_t>(it.slot) * (kBlk * kDim);
@@ -288,10 +345,76 @@ void fwd_kernel_bf16(FwdParams p) {
       const f32x4 v = *reinterpret_cast<const f32x4*>(lds_kv + (cc >> 3) * kTile + tile_off_bf16(row, cc & 7));
       *reinterpret_cast<f32x4*>(po + row * kDim + cc * 4) = v;
     }
+    return;
+  }
+
+  // ---- global row: merge the four waves' (m, l, O~) in LDS.  Wave w then owns query rows
+  // 16w .. 16w+15; a lane owns 16 d columns of one row.
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+    if (hf == 0) {
+      mrg_m[wv][q * 32 + col] = (m_ref[q] == neg_inf() || !(l_tot[q] > 0.f)) ? neg_inf() : m_ref[q] * c;
+      mrg_l[wv][q * 32 + col] = l_tot[q];
+    }
+  __syncthreads();  // all four waves of a global workgroup arrive here
+  {
+    const int q = wv * 16 + (lane >> 2), part = lane & 3;
+    float M = neg_inf();
+#pragma unroll
+    for (int v = 0; v < kFwdWaves; ++v) M = fmaxf(M, mrg_m[v][q]);
+    f32x4 acc[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float L = 0.f;
+    if (M != neg_inf()) {
+#pragma unroll
+      for (int v = 0; v < kFwdWaves; ++v) {
+        const float mv = mrg_m[v][q];
+        const float wgt = (mv == neg_inf()) ? 0.f : fast_exp2(mv - M);
+        L += mrg_l[v][q] * wgt;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int cc = part * 4 + e;
+          const f32x4 x =
+              *reinterpret_cast<const f32x4*>(lds_all[v] + (cc >> 3) * kTile + tile_off_bf16(q, cc & 7));
+#pragma unroll
+          for (int z = 0; z < 4; ++z) acc[e][z] += x[z] * wgt;
+        }
+      }
+    }
+    const size_t row = row_blk + q;
+    if (it.nchunks == 1) {
+      const float inv = L > 0.f ? 1.f / L : 0.f;
+      if (part == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
+      bf16x8 v0, v1;
+#pragma unroll
+      for (int z = 0; z < 4; ++z) {
+        v0[z] = static_cast<__bf16>(acc[0][z] * inv);
+        v0[4 + z] = static_cast<__bf16>(acc[1][z] * inv);
+        v1[z] = static_cast<__bf16>(acc[2][z] * inv);
+        v1[4 + z] = static_cast<__bf16>(acc[3][z] * inv);
+      }
+      bf16x8* dst = reinterpret_cast<bf16x8*>(static_cast<__bf16*>(p.O) + row * kDim + part * 16);
+      dst[0] = v0;
+      dst[1] = v1;
+    } else {
+      // one of several workgroups of a long global row: merged partial triple for the merge kernel
+      float* pml = p.part_ml + static_cast<size_t>(it.slot) * (2 * kBlk);
+      if (part == 0) {
+        pml[q] = L > 0.f ? M : neg_inf();
+        pml[kBlk + q] = L;
+      }
+      f32x4* dst =
+          reinterpret_cast<f32x4*>(p.part_o + static_cast<size_t>(it.slot) * (kBlk * kDim) + q * kDim + part * 16);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dst[e] = acc[e];
+    }
   }
 }
 
-int launch_fwd_bf16_main(const FwdParams& p, unsigned grid, hipStream_t stream) {
+int launch_fwd_bf16_main(const FwdParams& p, hipStream_t stream) {
+  const unsigned grid = static_cast<unsigned>(kXcd) * p.geo.bh_rounds * (p.geo.g_wgs + p.geo.s_wgs);
+  if (grid == 0) return BB_OK;
   hipLaunchKernelGGL(fwd_kernel_bf16, dim3(grid), dim3(kFwdThreads), 0, stream, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {

@@ -6,6 +6,21 @@
 
 namespace bb {
 
+// Work decomposition of the bf16 forward.  Workgroups have four independent waves.
+//   sparse workgroup: four consecutive items (non-global query block x slice of 8 key blocks);
+//   global workgroup: one global query block x up to 64 key blocks, 16 per wave, merged in LDS.
+// A global row longer than 64 key blocks takes several workgroups whose merged partial
+// results go through the merge kernel, as do sparse rows with more than one slice.
+constexpr int kGlobalWaveLen = 16;  // key blocks per wave of a global workgroup
+struct Bf16Geom {
+  int ng;        // workgroups per global row: ceil(nb / 64)
+  int cs;        // slices per non-global row
+  int n_sitems;  // (nb - g) * cs
+  int s_wgs;     // sparse workgroups per (batch, head): ceil(n_sitems / 4)
+  int g_wgs;     // global workgroups per (batch, head): g * ng
+  int bh_rounds; // ceil(B*H / 8)
+};
+
 struct FwdParams {
   const void* Q;
   const void* K;
@@ -18,14 +33,18 @@ struct FwdParams {
   float* part_ml;  // [slots][2][64]  their running maxima (log2 units) and sums
   int B, H, BH, n, nb, g, w, r, global_mode;
   float c;  // scale * log2(e)
-  RowSplit split;
+  RowSplit split;  // decomposition used by the fp32 kernel
+  Bf16Geom geo;    // decomposition used by the bf16 kernel
+  // rows whose slices the merge kernel combines: cmb_g_rows global rows of cmb_g_n slices each
+  // (slots first), then cmb_s_rows non-global rows of cmb_s_n slices; slots_per_bh in total
+  int cmb_g_rows, cmb_g_n, cmb_s_rows, cmb_s_n, slots_per_bh;
 };
 
 // Enqueues the fused forward kernel and, if any row is split, the merge kernel.
 int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream);
 
 // The tuned bf16 main kernel (defined in fwd_bf16.hip); launch_fwd calls it.
-int launch_fwd_bf16_main(const FwdParams& p, unsigned grid, hipStream_t stream);
+int launch_fwd_bf16_main(const FwdParams& p, hipStream_t stream);
 
 }  // namespace bb
 #endif  // BB_FWD_KERNELS_H_

@@ -187,23 +187,20 @@ constexpr int kCombineSplit = 4;  // workgroups per 64-query block
 template <bool BF16>
 __global__ __launch_bounds__(kCombineThreads) void fwd_combine_kernel(FwdParams p) {
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
-  const RowSplit& s = p.split;
-  const int nglob_rows = s.cg > 1 ? p.g : 0;
-  const int nsparse_rows = s.cs > 1 ? p.nb - p.g : 0;
-  const int rows_per_bh = nglob_rows + nsparse_rows;
+  const int rows_per_bh = p.cmb_g_rows + p.cmb_s_rows;
   const int part = blockIdx.x % kCombineSplit;
   const int rowid = blockIdx.x / kCombineSplit;
   const int bh = rowid / rows_per_bh, rr = rowid % rows_per_bh;
   int j, nchunks, slot0;
-  if (rr < nglob_rows) {
+  if (rr < p.cmb_g_rows) {
     j = pat.global_block(rr);
-    nchunks = s.cg;
-    slot0 = bh * s.slots_per_bh + rr * s.cg;
+    nchunks = p.cmb_g_n;
+    slot0 = bh * p.slots_per_bh + rr * p.cmb_g_n;
   } else {
-    const int t = rr - nglob_rows;
+    const int t = rr - p.cmb_g_rows;
     j = pat.sparse_block(t);
-    nchunks = s.cs;
-    slot0 = bh * s.slots_per_bh + (s.cg > 1 ? p.g * s.cg : 0) + t * s.cs;
+    nchunks = p.cmb_s_n;
+    slot0 = bh * p.slots_per_bh + p.cmb_g_rows * p.cmb_g_n + t * p.cmb_s_n;
   }
   const int q = part * 16 + (threadIdx.x >> 4), d0 = (threadIdx.x & 15) * 4;
   const float* ml = p.part_ml + static_cast<size_t>(slot0) * (2 * kBlk) + q;
@@ -260,17 +257,17 @@ bool launch_failed(const char* what) {
 }  // namespace
 
 int launch_fwd(const FwdParams& p, bool bf16, hipStream_t stream) {
-  const RowSplit& s = p.split;
-  const unsigned grid = static_cast<unsigned>(kXcd) * s.bh_rounds * s.items_per_bh;
-  if (grid == 0) return BB_OK;
   if (bf16) {
-    const int st = launch_fwd_bf16_main(p, grid, stream);
+    const int st = launch_fwd_bf16_main(p, stream);
     if (st != BB_OK) return st;
   } else {
+    const RowSplit& s = p.split;
+    const unsigned grid = static_cast<unsigned>(kXcd) * s.bh_rounds * s.items_per_bh;
+    if (grid == 0) return BB_OK;
     hipLaunchKernelGGL(fwd_kernel_f32, dim3(grid), dim3(kThreads), 0, stream, p);
     if (launch_failed("fwd_kernel_f32")) return BB_ERR_LAUNCH;
   }
-  const int rows_per_bh = (s.cg > 1 ? p.g : 0) + (s.cs > 1 ? p.nb - p.g : 0);
+  const int rows_per_bh = p.cmb_g_rows + p.cmb_s_rows;
   if (rows_per_bh > 0) {
     const unsigned cgrid = static_cast<unsigned>(p.BH) * rows_per_bh * kCombineSplit;
     if (bf16)

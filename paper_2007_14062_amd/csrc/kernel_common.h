@@ -168,18 +168,17 @@ __device__ __forceinline__ bool block_has_valid_key(const uint8_t* kmask, int bi
 
 // Key blocks attended by query block j of head h (App. D items 1-3 as a set
 // union, minus blocks without a valid key), slice `chunk` (see WorkItem) of the
-// ascending-by-candidate list.  Every lane of the calling wave takes part; the
-// slice is written to klist[0..count) and the count returned (wave uniform).
+// ascending-by-candidate list: entries [lo, lo+len).  Every lane of the calling wave takes
+// part; the slice is written to klist[0..count) and the count returned (wave uniform).
 // Candidate order: global blocks, window blocks, random blocks; a candidate is
 // dropped if an earlier component already holds it.
-__device__ __forceinline__ int build_key_list(const Pattern& pat, const int32_t* rand_idx, int r,
-                                              const uint8_t* kmask, int n, int bi, int h, int j,
-                                              bool row_global, int chunk, int* klist) {
+__device__ __forceinline__ int build_key_list_range(const Pattern& pat, const int32_t* rand_idx, int r,
+                                                    const uint8_t* kmask, int n, int bi, int h, int j,
+                                                    bool row_global, int lo, int len, int* klist) {
   const int lane = lane_id();
   const int nb = pat.nb;
   const int ncand = row_global ? nb : pat.g + pat.w + r;
-  const int len = row_global ? kChunkGlobal : kChunk;
-  const int lo = chunk * len, hi = lo + len;
+  const int hi = lo + len;
   const int32_t* rrow = rand_idx ? rand_idx + (static_cast<size_t>(h) * nb + j) * r : nullptr;
   int base = 0;
   for (int c0 = 0; c0 < ncand && base < hi; c0 += 64) {
@@ -212,6 +211,14 @@ __device__ __forceinline__ int build_key_list(const Pattern& pat, const int32_t*
   int cnt = base - lo;
   cnt = cnt < 0 ? 0 : (cnt > len ? len : cnt);
   return cnt;
+}
+
+// The same with the slice given by its number (see WorkItem).
+__device__ __forceinline__ int build_key_list(const Pattern& pat, const int32_t* rand_idx, int r,
+                                              const uint8_t* kmask, int n, int bi, int h, int j,
+                                              bool row_global, int chunk, int* klist) {
+  const int len = row_global ? kChunkGlobal : kChunk;
+  return build_key_list_range(pat, rand_idx, r, kmask, n, bi, h, j, row_global, chunk * len, len, klist);
 }
 
 // 64-bit validity mask of the keys of block k (bit t = key k*64+t is valid).
