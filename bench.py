@@ -4,7 +4,7 @@
 
 A step is one pass of the hot path over one synthetic batch of the BERT-base-shaped
 workload (bf16, B=4, H=12, n=4096, d=64, b=64, g/w/r = 2/3/3 blocks): the forward call
-bigbird_attn_fwd (fused kernel + merge of the split global rows).  Inputs are resident
+bigbird_attn_fwd (one fused kernel; the global rows are merged inside it).  Inputs are resident
 in HBM before the timed region.  Prints ONE JSON line.
 
 metric/value: useful TFLOP/s = 4 b^2 d flop per (query block, key block) pair of the
@@ -217,7 +217,7 @@ def main():
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": measured_traffic_bytes(),
-                     "kernel": "fwd_kernel<bf16> (+ fwd_combine_kernel, same timed region)"},
+                     "kernel": "bb::fwd_kernel_bf16 (the only kernel of a forward call at this size)"},
     }
     if not args.skip_backward:
         result["fwd_bwd_cfg4"] = time_fwd_bwd(bb, torch, dev, max(1, args.steps // 4), max(1, args.warmup // 4))
