@@ -54,16 +54,21 @@ __device__ __forceinline__ const char* uniform_ptr(const char* p) {
 // 16 bytes.  Instruction ii fills LDS rows 8*ii .. 8*ii+7 linearly (lane l lands on row
 // l/8, chunk position l%8) and fetches, for that place, the chunk the swizzle stores
 // there.  The swizzle depends on row bits 1..3, i.e. on l/8 and on the parity of ii:
-// voff[0] / voff[1] are the per-lane byte offsets for even / odd ii.
+// voff[0] / voff[1] are the per-lane byte offsets for even / odd ii.  The instruction's
+// immediate offset moves the global and the LDS address alike, so four instructions
+// share one base pair (M0, scalar address) and no vector arithmetic is needed.
 __device__ __forceinline__ void tile_load_async_wave(const char* gtile_, unsigned lds, const unsigned (&voff)[2]) {
   const char* gtile = uniform_ptr(gtile_);  // wave-uniform by construction: keep it in scalar registers
 #pragma unroll
-  for (int ii = 0; ii < 8; ++ii)
+  for (int hh = 0; hh < 2; ++hh)
     asm volatile(
-        "s_mov_b32 m0, %2\n\t"
-        "global_load_lds_dwordx4 %0, %1"
+        "s_mov_b32 m0, %3\n\t"
+        "global_load_lds_dwordx4 %0, %2\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
+        "global_load_lds_dwordx4 %0, %2 offset:2048\n\t"
+        "global_load_lds_dwordx4 %1, %2 offset:3072"
         :
-        : "v"(voff[ii & 1] + ii * 1024), "s"(gtile), "s"(lds + ii * 1024)
+        : "v"(voff[0]), "v"(voff[1]), "s"(gtile + hh * 4096), "s"(lds + hh * 4096)
         : "memory");  // M0 is written here; nothing else in this kernel reads M0
 }
 
