@@ -51,14 +51,16 @@ def device_inputs(wl, torch, dev):
     return t, out
 
 
-def time_cpu_oracle(wl, t, rand_idx, sample_heads: int):
-    """Oracle forward on batches 0-1, the first `sample_heads` heads, all host cores NumPy uses."""
+def time_cpu_oracle(wl, t, rand_idx, sample_heads: int, repeats: int = 2):
+    """Oracle forward on every batch, the first `sample_heads` heads, `repeats` times over
+    (mean time of one pass), on all host cores NumPy uses."""
     import oracle
-    Q, K, V = (t[x][:2, :sample_heads] for x in ("Q", "K", "V"))
+    Q, K, V = (t[x][:, :sample_heads] for x in ("Q", "K", "V"))
     t0 = time.perf_counter()
-    oracle.attn_fwd(Q, K, V, rand_idx[:sample_heads], wl.b, wl.g, wl.w, wl.scale)
-    dt = time.perf_counter() - t0
-    pairs = 2 * oracle.count_block_pairs(rand_idx[:sample_heads], wl.n, wl.b, wl.g, wl.w)
+    for _ in range(repeats):
+        oracle.attn_fwd(Q, K, V, rand_idx[:sample_heads], wl.b, wl.g, wl.w, wl.scale)
+    dt = (time.perf_counter() - t0) / repeats
+    pairs = wl.B * oracle.count_block_pairs(rand_idx[:sample_heads], wl.n, wl.b, wl.g, wl.w)
     try:
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
@@ -71,8 +73,8 @@ def time_cpu_oracle(wl, t, rand_idx, sample_heads: int):
         "unit": "useful TFLOP/s",
         "cores": cores,
         "kind": "oracle",
-        "sample": f"forward of batches 0-1, heads 0..{sample_heads - 1} of {wl.name} "
-                  f"(fp64 dense-mask NumPy oracle, {dt:.2f} s)",
+        "sample": f"forward of all {wl.B} batches, heads 0..{sample_heads - 1} of {wl.name}, "
+                  f"{repeats} passes (fp64 dense-mask NumPy oracle, {dt:.2f} s per pass)",
         "seconds": dt,
     }
 

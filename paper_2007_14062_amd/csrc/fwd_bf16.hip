@@ -13,7 +13,11 @@
 //   * The wave's queries form two 32-column MFMA tiles (A, B).  Every K and V^T
 //     operand fetched from LDS feeds two MFMAs (one per tile), which halves the LDS
 //     traffic per flop, and the tiles ping-pong: while the vector ALU exponentiates
-//     tile A the matrix pipe computes tile B's scores, and so on.
+//     tile A the matrix pipe computes tile B's scores; tile A's probabilities then wait
+//     in registers and its share of P V runs under tile B's exponentials.  The issue
+//     order (one MFMA, a handful of vector instructions, ...) is pinned with scheduling
+//     group barriers: left alone the compiler issues the MFMAs back to back, and a wave
+//     cannot issue anything else while it queues them.
 //   * K and V tiles go global -> LDS directly (no registers in between), one 8 KB
 //     buffer each: a tile is read out into operand registers in one burst and the
 //     next block's load is issued at once, so it has a whole block of work to land.
@@ -126,13 +130,6 @@ void fwd_kernel_bf16(FwdParams p) {
   }
   const int bi = it.bh / p.H, h = it.bh % p.H;
 
-  const int cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
-                                       list_lo, list_len, klist);
-  // same wave wrote and reads the list: LDS keeps a wave's accesses in order, the compiler must too
-  asm volatile("" ::: "memory");
-  const int kl = klist[lane & (kGlobalWaveLen - 1)];  // lane t holds list entry t % 16
-  auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
-
   const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
   const size_t qrow0 = bh_row0 + it.j * kBlk + col;  // tile A row of this lane; tile B is 32 rows on
   const char* kbase = static_cast<const char*>(p.K) + bh_row0 * (kDim * 2);
@@ -146,11 +143,20 @@ void fwd_kernel_bf16(FwdParams p) {
   }
   const unsigned lds_k_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_k));
   const unsigned lds_v_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_v));
-  auto tile_off = [&](int i) { return static_cast<size_t>(key_block(i)) * kTile; };
 
-  if (cnt > 0) {
-    tile_load_async_wave(kbase + tile_off(0), lds_k_a, voff);
-    tile_load_async_wave(vbase + tile_off(0), lds_v_a, voff);
+  // The first key block is nearly always known before the list is: a global row's slice starts
+  // at its own offset unless padding removed blocks before it, every other row starts with the
+  // first global block.  Its tiles are asked for now, so that their flight overlaps the reads
+  // of the pattern table instead of following them.
+  int spec = -1;
+  if (it.row_global) {
+    if (list_lo < p.nb) spec = list_lo;
+  } else if (it.chunk == 0 && p.g > 0) {
+    spec = pat.global_block(0);
+  }
+  if (spec >= 0) {
+    tile_load_async_wave(kbase + static_cast<size_t>(spec) * kTile, lds_k_a, voff);
+    tile_load_async_wave(vbase + static_cast<size_t>(spec) * kTile, lds_v_a, voff);
   }
 
   // Q^T operands (B of S^T = K Q^T) of the two query tiles: lane holds query `col`
@@ -163,6 +169,27 @@ void fwd_kernel_bf16(FwdParams p) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) qb[q][ks] = qp[ks * 2 + hf];
   }
+
+  const int cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
+                                       list_lo, list_len, klist);
+  // same wave wrote and reads the list: LDS keeps a wave's accesses in order, the compiler must too
+  asm volatile("" ::: "memory");
+  const int kl = klist[lane & (kGlobalWaveLen - 1)];  // lane t holds list entry t % 16
+  auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
+  auto tile_off = [&](int i) { return static_cast<size_t>(key_block(i)) * kTile; };
+
+  if (cnt == 0 || key_block(0) != spec) {
+    // wrong guess (or none): let the guessed tiles land before the buffers are reused or left
+    if (spec >= 0) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      asm volatile("" ::: "memory");
+    }
+    if (cnt > 0) {
+      tile_load_async_wave(kbase + tile_off(0), lds_k_a, voff);
+      tile_load_async_wave(vbase + tile_off(0), lds_v_a, voff);
+    }
+  }
+
   // The compiler settles the Q loads here, once, instead of at the first use inside the
   // loop (where its conservative wait would drain the tile loads).
 #pragma unroll
@@ -198,44 +225,27 @@ void fwd_kernel_bf16(FwdParams p) {
     asm volatile("" ::: "memory");
     if (more) tile_load_async_wave(kbase + next_off, lds_k_a, voff);
 
-    // ---- S^T = K Q^T for both query tiles (rows = 64 keys = two MFMA tiles each)
     f32x16 s[2][2];
-    zero_acc(s[0]);
-    zero_acc(s[1]);
+    auto scores = [&](int q, int ks) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+      for (int t = 0; t < 2; ++t) {
+        if (ks == 0) {
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-        s[0][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[0][ks], s[0][t], 0, 0, 0);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-        s[1][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[1][ks], s[1][t], 0, 0, 0);
-
-    if (vbits != ~0ull) {  // partly padded block: masked keys get -inf
+          for (int r = 0; r < 16; ++r) s[q][t][r] = 0.f;
+        }
+        s[q][t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[q][ks], s[q][t], 0, 0, 0);
+      }
+    };
+    auto mask_scores = [&](int q) {
       const uint64_t mine = vbits >> (hf * 4);
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r)
-            if (!((mine >> (t * 32 + acc_row(r, 0))) & 1)) s[q][t][r] = neg_inf();
-    }
-
-    // ---- V(i): wait (K(i+1)'s loads, if any, are younger), fetch all V^T operand pieces
-    if (more)
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
-    else
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-    asm volatile("" ::: "memory");
-    bf16x8 va[2][4];
-    to.read(lds_v, va);
-
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      // online softmax of tile q, base 2, lazily moved reference
+        for (int r = 0; r < 16; ++r)
+          if (!((mine >> (t * 32 + acc_row(r, 0))) & 1)) s[q][t][r] = neg_inf();
+    };
+    // online softmax of tile q, base 2, lazily moved reference: returns the exponent offset
+    auto tile_reference = [&](int q) {
       float mloc = neg_inf();
 #pragma unroll
       for (int t = 0; t < 2; ++t)
@@ -253,32 +263,75 @@ void fwd_kernel_bf16(FwdParams p) {
           for (int r = 0; r < 16; ++r) o[q][dt][r] *= alpha;
         m_ref[q] = m_new;
       }
-      const float mc = (m_ref[q] == neg_inf()) ? 0.f : m_ref[q] * c;
-
-      // four groups of 16 keys: exponentials, then the group's share of O^T += V^T P^T
+      return (m_ref[q] == neg_inf()) ? 0.f : m_ref[q] * c;
+    };
+    // probabilities of 16 keys (group sg) of tile q as a B operand; row sums on the side
+    auto probs = [&](int q, int sg, float mc) {
+      bf16x8 pb;
 #pragma unroll
-      for (int sg = 0; sg < 4; ++sg) {
-        bf16x8 pb;
-#pragma unroll
-        for (int kk = 0; kk < 8; kk += 2) {
-          const int t = sg >> 1, r = (sg & 1) * 8 + kk;
-          const float p0 = fast_exp2(__builtin_fmaf(s[q][t][r], c, -mc));
-          const float p1 = fast_exp2(__builtin_fmaf(s[q][t][r + 1], c, -mc));
-          const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
-          pb[kk] = pk[0];
-          pb[kk + 1] = pk[1];
-          l_run[q] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[q], false);
-        }
-        if (q == 0 && sg == 0) {
-          // every V^T piece is in registers now: the buffer can take V(i+1)
-          __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
-          asm volatile("" ::: "memory");
-          if (more) tile_load_async_wave(vbase + next_off, lds_v_a, voff);
-        }
-#pragma unroll
-        for (int dt = 0; dt < 2; ++dt)
-          o[q][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pb, o[q][dt], 0, 0, 0);
+      for (int kk = 0; kk < 8; kk += 2) {
+        const int t = sg >> 1, r = (sg & 1) * 8 + kk;
+        const float p0 = fast_exp2(__builtin_fmaf(s[q][t][r], c, -mc));
+        const float p1 = fast_exp2(__builtin_fmaf(s[q][t][r + 1], c, -mc));
+        const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+        pb[kk] = pk[0];
+        pb[kk + 1] = pk[1];
+        l_run[q] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[q], false);
       }
+      return pb;
+    };
+
+    // ---- phase 1: scores of tile A
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) scores(0, ks);
+    if (vbits != ~0ull) mask_scores(0);
+
+    // ---- phase 2: tile A's exponentials on the vector ALU while the matrix pipe computes tile
+    // B's scores; the probabilities wait in registers for V
+    const float mc_a = tile_reference(0);
+    bf16x8 pa[4];
+#pragma unroll
+    for (int sg = 0; sg < 4; ++sg) {
+      scores(1, sg);
+      pa[sg] = probs(0, sg, mc_a);
+      asm volatile("" : "+v"(pa[sg]));  // computed here, not where it is used
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {  // issue order: one MFMA, a dozen vector instructions, ...
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 12, 0);
+    }
+    if (vbits != ~0ull) mask_scores(1);
+
+    // ---- V(i): wait (K(i+1)'s loads, if any, are younger), fetch all V^T operand pieces
+    if (more)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    asm volatile("" ::: "memory");
+    bf16x8 va[2][4];
+    to.read(lds_v, va);
+    const float mc_b = tile_reference(1);
+    __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+    asm volatile("" ::: "memory");
+    if (more) tile_load_async_wave(vbase + next_off, lds_v_a, voff);
+
+    // ---- phase 3: tile B's exponentials while the matrix pipe does tile A's share of
+    // O^T += V^T P^T, then tile B's
+#pragma unroll
+    for (int sg = 0; sg < 4; ++sg) {
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+        o[0][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pa[sg], o[0][dt], 0, 0, 0);
+      const bf16x8 pb = probs(1, sg, mc_b);
+#pragma unroll
+      for (int dt = 0; dt < 2; ++dt)
+        o[1][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt][sg], pb, o[1][dt], 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 6, 0);
     }
   }
 
