@@ -33,7 +33,8 @@ struct BwdParams {
   int kv_items_per_bh;  // g*cq + (nb - g)
 };
 
-// Enqueues: row sums D, the dQ kernel, the dK/dV kernel and the fixed-order reductions.
+// Enqueues: the dQ kernel (which also computes the row sums D), the dK/dV kernel and the
+// fixed-order reductions.
 int launch_bwd_bf16(const BwdParams& p, hipStream_t stream);
 
 }  // namespace bb

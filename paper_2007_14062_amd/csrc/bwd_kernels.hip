@@ -7,7 +7,8 @@
 // Two gather kernels, no atomics:
 //   * bwd_dq_kernel walks the key-block list of a query block (the forward's
 //     decomposition): S^T, dP^T and dS^T are [keys x queries] tiles, one lane per
-//     query, and dQ^T += K^T dS^T.
+//     query, and dQ^T += K^T dS^T.  It also computes the row sums D (and leaves them
+//     in the workspace for the second kernel).
 //   * bwd_dkv_kernel walks the query-block list of a key block -- the inverse of the
 //     pattern: the global query blocks, the window, and the rows of rand_idx that
 //     name this key block (found by scanning the head's table) -- with S, dP, dS as
@@ -48,37 +49,17 @@ __device__ __forceinline__ void store_acc_rows(float* dst_row, const f32x16 (&a)
 
 }  // namespace
 
-// D_i = sum_c dO_ic O_ic and LSE_i log2(e) (with +inf where the forward found no valid
-// key, so that the recomputed probabilities of such a row are 0).  8 lanes per row.
-__global__ __launch_bounds__(256) void bwd_preprocess_kernel(BwdParams p) {
-  const size_t rows = static_cast<size_t>(p.BH) * p.n;
-  const size_t row = static_cast<size_t>(blockIdx.x) * 32 + (threadIdx.x >> 3);
-  const int part = threadIdx.x & 7;
-  float acc = 0.f;
-  if (row < rows) {
-    const bf16x8 a = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.dO) + row * kDim)[part];
-    const bf16x8 b = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.O) + row * kDim)[part];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc += static_cast<float>(a[e]) * static_cast<float>(b[e]);
-  }
-  acc += __shfl_xor(acc, 1);
-  acc += __shfl_xor(acc, 2);
-  acc += __shfl_xor(acc, 4);
-  if (row < rows && part == 0) {
-    p.Dvec[row] = acc;
-    const float lse = p.LSE[row];
-    p.Lvec[row] = (lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;
-  }
-}
-
 // ---------------------------------------------------------------------------------------
 // dQ: one work item = (batch*head, query block j, slice of <= 8 key blocks of j's list)
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3)))
 void bwd_dq_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTile];
   __shared__ __attribute__((aligned(1024))) char lds_v[2 * kTile];
-  __shared__ int klist[kChunkMax];
+  // The key list lives in the second V buffer, which is not written before the first barrier of
+  // the loop; by then every lane holds its entry in a register.  32 KB of LDS per workgroup
+  // exactly: five workgroups fit a CU.
+  int* const klist = reinterpret_cast<int*>(lds_v + kTile);
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   WorkItem it;
@@ -118,8 +99,28 @@ void bwd_dq_kernel(BwdParams p) {
       dob[ks] = dp[ks * 2 + hf];
     }
   }
-  float lse2 = p.Lvec[qrow];
-  float dsum = p.Dvec[qrow];
+  // D_i = sum_c dO_ic O_ic and LSE_i log2(e) of this lane's query (+inf where the forward found
+  // no valid key, so that the recomputed probabilities of such a row are 0).  The lane pair
+  // (l, l+32) shares a query and holds complementary halves of its d range.  The first slice of
+  // a row also leaves both values in the workspace for the dK/dV kernel, which runs after this one.
+  float dsum, lse2;
+  {
+    const bf16x8* op = reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.O) + qrow * kDim);
+    float part = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const bf16x8 ob = op[ks * 2 + hf];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) part += static_cast<float>(dob[ks][e]) * static_cast<float>(ob[e]);
+    }
+    dsum = half_sum(part);
+    const float lse = p.LSE[qrow];
+    lse2 = (lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;
+    if (it.chunk == 0 && hf == 0) {
+      p.Dvec[qrow] = dsum;
+      p.Lvec[qrow] = lse2;
+    }
+  }
   // let the compiler settle these loads here, not inside the loop (see the forward kernel)
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qb[ks]), "+v"(dob[ks]));
@@ -504,11 +505,6 @@ bool launch_failed(const char* what) {
 }  // namespace
 
 int launch_bwd_bf16(const BwdParams& p, hipStream_t stream) {
-  const size_t rows = static_cast<size_t>(p.BH) * p.n;
-  hipLaunchKernelGGL(bwd_preprocess_kernel, dim3(static_cast<unsigned>((rows + 31) / 32)), dim3(256), 0,
-                     stream, p);
-  if (launch_failed("bwd_preprocess_kernel")) return BB_ERR_LAUNCH;
-
   const RowSplit& s = p.split;
   const unsigned qgrid = static_cast<unsigned>(kXcd) * s.bh_rounds * s.items_per_bh;
   hipLaunchKernelGGL(bwd_dq_kernel, dim3(qgrid), dim3(kThreads), 0, stream, p);
