@@ -80,6 +80,20 @@ def test_degenerate_patterns(g, w, r):
     check_full(t, ridx, 64, g, w, 0.125, tag=f"bwd g{g} w{w} r{r}")
 
 
+def test_summarisation_encoder_length_3072():
+    """nb = 48 (not a power of two; six slices per global row and column), B*H = 10."""
+    B, H, n, g, w, r = 1, 10, 3072, 2, 3, 3
+    t = inp.make_tensors(B, H, n, 64, 57, "bf16", with_dO=True)
+    ridx = bb.bigbird_make_rand_idx(H, n, 64, g, w, r, 13)
+    dQ, dK, dV = run_fwd_bwd(t, ridx, g, w, 0.125)
+    for h in (0, 9):
+        sub = {k: v[:, h:h + 1] for k, v in t.items() if k in ("Q", "K", "V", "dO")}
+        rQ, rK, rV = oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], ridx[h:h + 1], 64, g, w, 0.125)
+        errs = [np.abs(to_host(x)[:, h:h + 1] - r_).max() for x, r_ in ((dQ, rQ), (dK, rK), (dV, rV))]
+        print(f"bwd n=3072 head {h}: max|ddQ|={errs[0]:.3e} max|ddK|={errs[1]:.3e} max|ddV|={errs[2]:.3e}")
+        assert max(errs) <= TOL, (h, errs)
+
+
 def test_single_block_sequence():
     t = inp.make_tensors(2, 1, 64, 64, 20, "bf16", with_dO=True)
     empty = np.full((1, 1, 0), -1, dtype=np.int32)

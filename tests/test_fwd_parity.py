@@ -94,6 +94,25 @@ def test_degenerate_patterns(g, w, r):
     check_full(t, ridx, "bf16", 64, g, w, 0.125, tag=f"g{g} w{w} r{r}")
 
 
+@pytest.mark.parametrize("n", [2048, 3072])
+def test_summarisation_encoder_lengths(n):
+    """Encoder lengths of the summarisation experiments (App. E.5): nb = 32 and 48 (not a power
+    of two), 16 heads as in the large model (B*H = 16: two rounds over the 8 dies), two of the
+    heads compared in full."""
+    B, H, g, w, r = 1, 16, 2, 3, 3
+    t = inp.make_tensors(B, H, n, 64, 31 + n, "bf16")
+    ridx = bb.bigbird_make_rand_idx(H, n, 64, g, w, r, 11)
+    O, LSE = run_fwd(t, ridx, "bf16", g, w, 0.125)
+    Oh, Lh = to_host(O), to_host(LSE)
+    for h in (3, 15):
+        sub = {k: v[:, h:h + 1] for k, v in t.items() if k in ("Q", "K", "V")}
+        Oref, Lref = oracle.attn_fwd(sub["Q"], sub["K"], sub["V"], ridx[h:h + 1], 64, g, w, 0.125)
+        err_o = np.abs(Oh[:, h:h + 1] - Oref).max()
+        err_l = np.abs(Lh[:, h:h + 1] - Lref).max()
+        print(f"n={n} head {h}: max|dO|={err_o:.3e} max|dLSE|={err_l:.3e}")
+        assert err_o <= TOL["bf16"] and err_l <= TOL["bf16"], (n, h, err_o, err_l)
+
+
 def test_single_block_sequence():
     t = inp.make_tensors(2, 1, 64, 64, 10, "f32")
     empty = np.full((1, 1, 0), -1, dtype=np.int32)
