@@ -20,7 +20,7 @@ struct BwdParams {
   float* dV;
   const int32_t* rand_idx;
   const uint8_t* kmask;
-  float* Dvec;     // [B*H*n]  D_i = sum_c dO_ic O_ic
+  float* Dvec;     // [B*H*n]  -D_i, D_i = sum_c dO_ic O_ic (written by the dQ kernel)
   float* Lvec;     // [B*H*n]  LSE_i * log2(e); +inf for rows without a valid key
   float* part_dq;  // [slots][64][64] partial dQ of split rows (slots as in the forward)
   float* part_dk;  // [B*H*g*cq][64][64] partial dK of global key blocks

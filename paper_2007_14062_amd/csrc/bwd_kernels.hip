@@ -52,13 +52,12 @@ __device__ __forceinline__ void store_acc_rows(float* dst_row, const f32x16 (&a)
 // ---------------------------------------------------------------------------------------
 // dQ: one work item = (batch*head, query block j, slice of <= 8 key blocks of j's list)
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(3)))
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void bwd_dq_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTile];
   __shared__ __attribute__((aligned(1024))) char lds_v[2 * kTile];
   // The key list lives in the second V buffer, which is not written before the first barrier of
-  // the loop; by then every lane holds its entry in a register.  32 KB of LDS per workgroup
-  // exactly: five workgroups fit a CU.
+  // the loop; by then every lane holds its entry in a register.
   int* const klist = reinterpret_cast<int*>(lds_v + kTile);
 
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
@@ -117,7 +116,7 @@ void bwd_dq_kernel(BwdParams p) {
     const float lse = p.LSE[qrow];
     lse2 = (lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;
     if (it.chunk == 0 && hf == 0) {
-      p.Dvec[qrow] = dsum;
+      p.Dvec[qrow] = -dsum;  // negated: the other kernel starts its dP accumulators from it
       p.Lvec[qrow] = lse2;
     }
   }
@@ -131,6 +130,9 @@ void bwd_dq_kernel(BwdParams p) {
   f32x16 dq[2];
   zero_acc(dq);
   const float c = p.c;
+  f32x16 neg_d;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) neg_d[r] = -dsum;
 
   for (int i = 0; i < cnt; ++i) {
     const int buf = i & 1;
@@ -149,9 +151,12 @@ void bwd_dq_kernel(BwdParams p) {
     const char* vt = lds_v + buf * kTile;
 
     // S^T = K Q^T and dP^T = V dO^T: rows = 64 keys, columns = this wave's 32 queries
+    // (dP^T starts from -D: every element of a lane's accumulators belongs to the lane's query,
+    // so the subtraction in dS = P o (dP - D) costs no vector instruction)
     f32x16 s[2], dp[2];
     zero_acc(s);
-    zero_acc(dp);
+    dp[0] = neg_d;
+    dp[1] = neg_d;
     {
       bf16x8 ka[2][4];
       so.read(kt, ka);
@@ -184,7 +189,7 @@ void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float pv = fast_exp2(__builtin_fmaf(s[t][r], c, -lse2));
-        s[t][r] = pv * (dp[t][r] - dsum);
+        s[t][r] = pv * dp[t][r];
       }
     bf16x8 dsb[4];
     pack_acc_bf16(s, dsb);
@@ -360,9 +365,20 @@ void bwd_dkv_kernel(BwdParams p) {
     const char* dot = lds_do + buf * kTile;
 
     // S = Q K^T and dP = dO V^T: rows = 64 queries of block j, columns = this wave's 32 keys
+    // (dP starts from -D_q, staged with the tiles: element r of an accumulator belongs to query
+    // row acc_row(r), so dS = P o (dP - D) needs no subtraction afterwards)
+    const float* lq = lds_lse + buf * kBlk;
+    const float* dq = lds_d + buf * kBlk;
     f32x16 s[2], dp[2];
     zero_acc(s);
-    zero_acc(dp);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dq + t * 32 + acc_row(r4 * 4, hf));
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dp[t][r4 * 4 + e] = d4[e];
+      }
     {
       bf16x8 qa[2][4];
       so.read(qt, qa);
@@ -382,22 +398,19 @@ void bwd_dkv_kernel(BwdParams p) {
           dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[t][ks], vb[ks], dp[t], 0, 0, 0);
     }
     // P = 2^(S c - LSE_q log2e) (0 for a padded key), dS = P o (dP - D_q); q runs along the rows
-    const float* lq = lds_lse + buf * kBlk;
-    const float* dq = lds_d + buf * kBlk;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
         const int q0 = t * 32 + acc_row(r4 * 4, hf);
         const f32x4 l4 = *reinterpret_cast<const f32x4*>(lq + q0);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dq + q0);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = r4 * 4 + e;
           float pv = fast_exp2(__builtin_fmaf(s[t][r], c, -l4[e]));
           pv = key_valid ? pv : 0.f;
           s[t][r] = pv;
-          dp[t][r] = pv * (dp[t][r] - d4[e]);
+          dp[t][r] = pv * dp[t][r];
         }
       }
     bf16x8 pb[4], dsb[4];
