@@ -22,13 +22,15 @@ constexpr int kLgkmcnt0 = 15 | (3 << 14) | (7 << 4);  // wait for all LDS reads,
 // these loads: it would otherwise drain them before every LDS read.  The waits
 // are placed by hand (loads return in order, so vmcnt(N) is exact).
 __device__ __forceinline__ void tile_load_async(const char* gtile, unsigned lds, unsigned voff) {
+  // the instruction offset moves the global and the LDS address alike: two base pairs per tile
 #pragma unroll
-  for (int ii = 0; ii < 4; ++ii)
+  for (int hh = 0; hh < 2; ++hh)
     asm volatile(
         "s_mov_b32 m0, %2\n\t"
-        "global_load_lds_dwordx4 %0, %1"
+        "global_load_lds_dwordx4 %0, %1\n\t"
+        "global_load_lds_dwordx4 %0, %1 offset:2048"
         :
-        : "v"(voff + ii * 2048), "s"(gtile), "s"(lds + ii * 2048)
+        : "v"(voff), "s"(gtile + hh * 4096), "s"(lds + hh * 4096)
         : "memory");  // M0 is written here; nothing else in this kernel reads M0
 }
 
