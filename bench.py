@@ -198,6 +198,13 @@ def main():
     ms = max(ev_ms, 1e-9)
     tflops = flops / (ms * 1e-3) / 1e12
 
+    props = torch.cuda.get_device_properties(dev)
+    clock_khz = getattr(props, "clock_rate", 0) or 0
+    device = {"name": props.name, "compute_units": props.multi_processor_count,
+              "max_clock_mhz": clock_khz / 1e3,
+              # the same formula as the published peak, with what the device reports
+              "bf16_mfma_peak_tflops_at_reported_clock":
+                  props.multi_processor_count * clock_khz * 1e3 * 4096 / 1e12 if clock_khz else None}
     result = {
         "metric": "useful TFLOP/s, BigBird block-sparse attention forward (n=4096, H=12, d=64, b=64)",
         "value": tflops,
@@ -216,6 +223,7 @@ def main():
                    "g": wl.g, "w": wl.w, "r": wl.r, "block_pairs": pairs,
                    "useful_gflop_per_step": flops / 1e9, "pass": "forward"},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / BF16_MFMA_PEAK_TFLOPS,
+        "device": device,
         "roofline": {"bound": "mfma", "achieved": tflops, "peak": BF16_MFMA_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tflops / BF16_MFMA_PEAK_TFLOPS,
                      "traffic": measured_traffic_bytes(),
