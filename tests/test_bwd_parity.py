@@ -162,6 +162,11 @@ def test_cfg4_sampled_heads():
     dOh = t["dO"].astype(np.float64)
     assert np.abs(hV.sum(axis=2) - dOh.sum(axis=2)).max() <= 0.5       # sums of 4096 bf16-rounded terms
     assert np.abs(hK.sum(axis=2)).max() <= 0.5
+    # dQ = scale dS K and dK = scale dS^T Q give sum(Q o dQ) = sum(K o dK) = sum(dS o S) per head
+    qdq = (t["Q"].astype(np.float64) * hQ).sum(axis=(2, 3))
+    kdk = (t["K"].astype(np.float64) * hK).sum(axis=(2, 3))
+    print("cfg4 sum(Q o dQ) vs sum(K o dK): max diff", np.abs(qdq - kdk).max(), "of", np.abs(qdq).max())
+    assert np.abs(qdq - kdk).max() <= 1e-3 * max(1.0, np.abs(qdq).max()) + 0.5
 
 
 def test_fp32_backward_is_refused_not_faked():

@@ -475,3 +475,17 @@ def test_backward_full_coverage_matches_dense_formula_by_loops():
     np.testing.assert_allclose(dQ[0, 0], wantQ, atol=1e-12)
     np.testing.assert_allclose(dK[0, 0], wantK, atol=1e-12)
     np.testing.assert_allclose(dV[0, 0], wantV, atol=1e-12)
+
+
+def test_scale_invariance_identity_of_the_gradients():
+    """S depends on Q and K only through Q K^T, so sum(Q o dQ) = sum(K o dK) per head (both equal
+    sum(dS o S)).  A wrong transpose, a dropped scale or a missing -D term breaks it."""
+    H, n, b, g, w, r, d = 2, 256, 16, 1, 3, 2, 8
+    tbl = make_rand_idx(H, n, b, g, w, r, seed=5)
+    rng = np.random.default_rng(5)
+    Q, K, V, dO = (rng.standard_normal((1, H, n, d)) for _ in range(4))
+    dQ, dK, dV = attn_bwd(Q, K, V, dO, tbl, b, g, w, 0.3)
+    qdq = (Q * dQ).sum(axis=(2, 3))
+    kdk = (K * dK).sum(axis=(2, 3))
+    np.testing.assert_allclose(qdq, kdk, rtol=1e-10, atol=1e-10)
+    assert np.abs(qdq).min() > 1e-3  # not trivially zero
