@@ -76,6 +76,40 @@ __device__ __forceinline__ void tile_load_async_wave(const char* gtile_, unsigne
         : "memory");  // M0 is written here; nothing else in this kernel reads M0
 }
 
+// Key-block list of a non-global row without a padding mask, from the row of the pattern table
+// that lanes 0 .. r-1 already hold in `rnd` (one entry per lane).  Same candidate order and
+// rules as build_key_list_range: global blocks, window blocks, random blocks; a candidate is
+// dropped if an earlier component already holds it.  Entries [lo, lo+len) go to klist.
+__device__ __forceinline__ int finish_key_list_sparse(const Pattern& pat, int r, int j, int rnd, int lo,
+                                                       int len, int* klist) {
+  const int lane = lane_id();
+  const int nb = pat.nb;
+  const int ncand = pat.g + pat.w + r;  // <= 64 (checked by the caller)
+  bool valid = false;
+  int k = -1;
+  const int t = lane - pat.g - pat.w;
+  const int mine = __shfl(rnd, t < 0 ? 0 : t);  // entry t of the row, for the lanes that stand for it
+  if (lane < pat.g) {
+    k = pat.global_block(lane);
+    valid = true;
+  } else if (lane < pat.g + pat.w) {
+    k = j - pat.half() + (lane - pat.g);
+    valid = k >= 0 && k < nb && !pat.is_global(k);
+  } else if (lane < ncand) {
+    k = mine;
+    valid = k >= 0 && k < nb && !pat.is_global(k) && !pat.in_window(j, k);
+  }
+  for (int u = 0; u < r; ++u) {
+    const int ku = __builtin_amdgcn_readlane(rnd, u);
+    if (u < t && ku == k) valid = false;
+  }
+  const uint64_t m = __ballot(valid);
+  const int rank = mask_rank(m);
+  if (valid && rank >= lo && rank < lo + len) klist[rank - lo] = k;
+  int cnt = static_cast<int>(__popcll(m)) - lo;
+  return cnt < 0 ? 0 : (cnt > len ? len : cnt);
+}
+
 }  // namespace
 
 __global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
@@ -148,6 +182,17 @@ void fwd_kernel_bf16(FwdParams p) {
   // at its own offset unless padding removed blocks before it, every other row starts with the
   // first global block.  Its tiles are asked for now, so that their flight overlaps the reads
   // of the pattern table instead of following them.
+  // For a non-global row without a padding mask the pattern-table row is asked for before
+  // anything else (one entry per lane, by inline asm so that it can be waited for by count:
+  // loads return in order, and the tile and Q loads issued after it need not have landed when
+  // the list is built).
+  const bool fast_list = !it.row_global && !p.kmask && p.rand_idx && p.r > 0 && p.g + p.w + p.r <= 64;
+  int rnd = -1;
+  if (fast_list) {
+    const int32_t* rrow = p.rand_idx + (static_cast<size_t>(h) * p.nb + it.j) * p.r + (lane < p.r ? lane : 0);
+    asm volatile("global_load_dword %0, %1, off" : "=v"(rnd) : "v"(rrow) : "memory");
+  }
+
   int spec = -1;
   if (it.row_global) {
     if (list_lo < p.nb) spec = list_lo;
@@ -170,8 +215,19 @@ void fwd_kernel_bf16(FwdParams p) {
     for (int ks = 0; ks < 4; ++ks) qb[q][ks] = qp[ks * 2 + hf];
   }
 
-  const int cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
-                                       list_lo, list_len, klist);
+  int cnt;
+  if (fast_list) {
+    // younger than the table load: the guessed tiles' 16 loads (if any) and the 8 Q loads
+    if (spec >= 0)
+      asm volatile("s_waitcnt vmcnt(24)" : "+v"(rnd)::"memory");
+    else
+      asm volatile("s_waitcnt vmcnt(8)" : "+v"(rnd)::"memory");
+    if (lane >= p.r) rnd = -1;
+    cnt = finish_key_list_sparse(pat, p.r, it.j, rnd, list_lo, list_len, klist);
+  } else {
+    cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global, list_lo,
+                               list_len, klist);
+  }
   // same wave wrote and reads the list: LDS keeps a wave's accesses in order, the compiler must too
   asm volatile("" ::: "memory");
   const int kl = klist[lane & (kGlobalWaveLen - 1)];  // lane t holds list entry t % 16
