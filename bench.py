@@ -201,7 +201,7 @@ def main():
     props = torch.cuda.get_device_properties(dev)
     clock_khz = getattr(props, "clock_rate", 0) or 0
     device = {"name": props.name, "compute_units": props.multi_processor_count,
-              "max_clock_mhz": clock_khz / 1e3,
+              "max_clock_mhz": clock_khz / 1e3 if clock_khz else None,   # not reported by every runtime
               # the same formula as the published peak, with what the device reports
               "bf16_mfma_peak_tflops_at_reported_clock":
                   props.multi_processor_count * clock_khz * 1e3 * 4096 / 1e12 if clock_khz else None}
