@@ -199,27 +199,19 @@ void fwd_kernel_bf16(FwdParams p) {
   } else if (it.chunk == 0 && p.g > 0) {
     spec = pat.global_block(0);
   }
-  if (spec >= 0) {
-    tile_load_async_wave(kbase + static_cast<size_t>(spec) * kTile, lds_k_a, voff);
-    tile_load_async_wave(vbase + static_cast<size_t>(spec) * kTile, lds_v_a, voff);
-  }
+  if (spec >= 0) tile_load_async_wave(kbase + static_cast<size_t>(spec) * kTile, lds_k_a, voff);
 
-  // Q^T operands (B of S^T = K Q^T) of the two query tiles: lane holds query `col`
-  // (+32 for tile B), d = 16*ks + 8*hf .. +8
-  bf16x8 qb[2][4];
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    const bf16x8* qp =
-        reinterpret_cast<const bf16x8*>(static_cast<const __bf16*>(p.Q) + (qrow0 + q * 32) * kDim);
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) qb[q][ks] = qp[ks * 2 + hf];
-  }
+  // The query block takes the same road as a key block: eight coalesced 1 KB loads into LDS
+  // (the V buffer, idle until the first block's second half), then operand reads.  Register
+  // loads of the operand layout would touch every row of the tile in each instruction and cost
+  // the address unit four times as many cache-line requests.
+  tile_load_async_wave(static_cast<const char*>(p.Q) + (bh_row0 + it.j * kBlk) * (kDim * 2), lds_v_a, voff);
 
   int cnt;
   if (fast_list) {
-    // younger than the table load: the guessed tiles' 16 loads (if any) and the 8 Q loads
+    // younger than the table load: the guessed K tile's 8 loads (if any) and Q's 8
     if (spec >= 0)
-      asm volatile("s_waitcnt vmcnt(24)" : "+v"(rnd)::"memory");
+      asm volatile("s_waitcnt vmcnt(16)" : "+v"(rnd)::"memory");
     else
       asm volatile("s_waitcnt vmcnt(8)" : "+v"(rnd)::"memory");
     if (lane >= p.r) rnd = -1;
@@ -234,24 +226,26 @@ void fwd_kernel_bf16(FwdParams p) {
   auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
   auto tile_off = [&](int i) { return static_cast<size_t>(key_block(i)) * kTile; };
 
-  if (cnt == 0 || key_block(0) != spec) {
-    // wrong guess (or none): let the guessed tiles land before the buffers are reused or left
-    if (spec >= 0) {
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-      asm volatile("" ::: "memory");
-    }
-    if (cnt > 0) {
-      tile_load_async_wave(kbase + tile_off(0), lds_k_a, voff);
-      tile_load_async_wave(vbase + tile_off(0), lds_v_a, voff);
-    }
+  // Q^T operands (B of S^T = K Q^T) of the two query tiles: lane holds query `col` (+32 for
+  // tile B), d = 16*ks + 8*hf .. +8 -- the "straight" fragments of the Q tile.
+  bf16x8 qb[2][4];
+  const StraightOffsets so(lane);
+  const bool guessed = cnt > 0 && key_block(0) == spec;
+  if (!guessed && cnt > 0) {
+    // wrong guess (or none): everything issued so far lands, then the right K tile is asked for
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    asm volatile("" ::: "memory");
+    tile_load_async_wave(kbase + tile_off(0), lds_k_a, voff);
+    so.read(lds_v, qb);
+  } else {
+    // Q was issued after the guessed K tile: when it has landed, so has K
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    asm volatile("" ::: "memory");
+    so.read(lds_v, qb);
   }
-
-  // The compiler settles the Q loads here, once, instead of at the first use inside the
-  // loop (where its conservative wait would drain the tile loads).
-#pragma unroll
-  for (int q = 0; q < 2; ++q)
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qb[q][ks]));
+  __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
+  asm volatile("" ::: "memory");
+  if (cnt > 0) tile_load_async_wave(vbase + tile_off(0), lds_v_a, voff);
 
   f32x16 o[2][2];  // [query tile][d tile]: O^T accumulators
   zero_acc(o[0]);
@@ -260,7 +254,6 @@ void fwd_kernel_bf16(FwdParams p) {
   float l_run[2] = {0.f, 0.f};              // this lane's share of sum 2^((s - m_ref) c)
   const float c = p.c;
   const float tau = kLazyLog2 / c;
-  const StraightOffsets so(lane);
   const TransposedOffsets to(lane);
   const bf16x2 ones = {static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)};
 
