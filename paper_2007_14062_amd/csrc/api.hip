@@ -119,12 +119,26 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   if (dtype == BB_BF16) {
     bb::Bf16Geom& q = p.geo;
-    q.ng = (p.nb + 4 * bb::kGlobalWaveLen - 1) / (4 * bb::kGlobalWaveLen);
     q.cs = p.split.cs;
     q.n_sitems = (p.nb - g) * q.cs;
     q.s_wgs = (q.n_sitems + 3) / 4;
-    q.g_wgs = g * q.ng;
     q.bh_rounds = p.split.bh_rounds;
+    // Global rows: 16 key blocks per wave (up to 64 per workgroup, merged in LDS).  When every
+    // workgroup of the launch is resident at once (two per CU, 32 CUs per die) the longest
+    // workgroup sets the run time, so the global rows are then cut twice as fine, into
+    // workgroups whose partial results the merge kernel combines -- if that finer grid still fits.
+    q.gw_len = bb::kGlobalWaveLen;
+    q.ng = (p.nb + 4 * q.gw_len - 1) / (4 * q.gw_len);
+    {
+      const int slots_per_die = 64;
+      const int fine_len = bb::kGlobalWaveLen / 2;
+      const int fine_ng = (p.nb + 4 * fine_len - 1) / (4 * fine_len);
+      if (p.nb > 4 * fine_len && q.bh_rounds * (g * fine_ng + q.s_wgs) <= slots_per_die) {
+        q.gw_len = fine_len;
+        q.ng = fine_ng;
+      }
+    }
+    q.g_wgs = g * q.ng;
     p.cmb_g_rows = q.ng > 1 ? g : 0;
     p.cmb_g_n = q.ng;
     p.cmb_s_rows = q.cs > 1 ? p.nb - g : 0;

@@ -145,8 +145,8 @@ void fwd_kernel_bf16(FwdParams p) {
       it.chunk = u;
       it.nchunks = geo.ng;
       it.slot = it.bh * p.slots_per_bh + row * geo.ng + u;
-      list_lo = (u * kFwdWaves + wv) * kGlobalWaveLen;
-      list_len = kGlobalWaveLen;
+      list_lo = (u * kFwdWaves + wv) * geo.gw_len;
+      list_len = geo.gw_len;
       if (it.bh >= p.BH) return;  // whole workgroup
     } else {
       q -= n_gpart;

@@ -11,9 +11,11 @@ namespace bb {
 //   global workgroup: one global query block x up to 64 key blocks, 16 per wave, merged in LDS.
 // A global row longer than 64 key blocks takes several workgroups whose merged partial
 // results go through the merge kernel, as do sparse rows with more than one slice.
-constexpr int kGlobalWaveLen = 16;  // key blocks per wave of a global workgroup
+constexpr int kGlobalWaveLen = 16;  // most key blocks a wave of a global workgroup takes
 struct Bf16Geom {
-  int ng;        // workgroups per global row: ceil(nb / 64)
+  int gw_len;    // key blocks per wave of a global workgroup: 16, or 8 when the whole grid fits
+                 // the chip at once (then the global rows alone would set the run time)
+  int ng;        // workgroups per global row: ceil(nb / (4 * gw_len))
   int cs;        // slices per non-global row
   int n_sitems;  // (nb - g) * cs
   int s_wgs;     // sparse workgroups per (batch, head): ceil(n_sitems / 4)
