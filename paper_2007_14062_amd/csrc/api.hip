@@ -119,7 +119,13 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   if (dtype == BB_BF16) {
     bb::Bf16Geom& q = p.geo;
-    q.cs = p.split.cs;
+    {
+      // a wave takes up to 16 key blocks of a non-global row; wider patterns are sliced
+      int sparse_ub = g + w + r;
+      if (sparse_ub > p.nb) sparse_ub = p.nb;
+      q.cs = (sparse_ub + bb::kGlobalWaveLen - 1) / bb::kGlobalWaveLen;
+      if (q.cs < 1) q.cs = 1;
+    }
     q.n_sitems = (p.nb - g) * q.cs;
     q.s_wgs = (q.n_sitems + 3) / 4;
     q.bh_rounds = p.split.bh_rounds;

@@ -158,8 +158,8 @@ void fwd_kernel_bf16(FwdParams p) {
       it.chunk = sitem % geo.cs;
       it.nchunks = geo.cs;
       it.slot = it.bh * p.slots_per_bh + p.cmb_g_rows * p.cmb_g_n + sitem;
-      list_lo = it.chunk * kChunk;
-      list_len = kChunk;
+      list_lo = it.chunk * kGlobalWaveLen;  // up to 16 key blocks per item (8 at the ITC base pattern)
+      list_len = kGlobalWaveLen;
     }
   }
   const int bi = it.bh / p.H, h = it.bh % p.H;

@@ -7,7 +7,8 @@
 namespace bb {
 
 // Work decomposition of the bf16 forward.  Workgroups have four independent waves.
-//   sparse workgroup: four consecutive items (non-global query block x slice of 8 key blocks);
+//   sparse workgroup: four consecutive items (non-global query block x slice of up to 16 key
+//   blocks: 8 at the ITC base pattern);
 //   global workgroup: one global query block x up to 64 key blocks, 16 per wave, merged in LDS.
 // A global row longer than 64 key blocks takes several workgroups whose merged partial
 // results go through the merge kernel, as do sparse rows with more than one slice.
@@ -16,7 +17,7 @@ struct Bf16Geom {
   int gw_len;    // key blocks per wave of a global workgroup: 16, or 8 when the whole grid fits
                  // the chip at once (then the global rows alone would set the run time)
   int ng;        // workgroups per global row: ceil(nb / (4 * gw_len))
-  int cs;        // slices per non-global row
+  int cs;        // slices per non-global row: ceil(min(g + w + r, nb) / 16)
   int n_sitems;  // (nb - g) * cs
   int s_wgs;     // sparse workgroups per (batch, head): ceil(n_sitems / 4)
   int g_wgs;     // global workgroups per (batch, head): g * ng
