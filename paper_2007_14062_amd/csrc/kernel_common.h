@@ -11,12 +11,13 @@ namespace bb {
 
 constexpr int kBlk = 64;      // block length b (App. E.1: 64 for every ITC model)
 constexpr int kDim = 64;      // head width d
-constexpr int kChunk = 8;     // key blocks per work item of a non-global row (= g+w+r of the ITC base pattern)
+constexpr int kChunk = 8;     // list entries per slice of a global row / global key column
+constexpr int kSparseChunk = 16;  // most key blocks per work item of a non-global row (the ITC base pattern has g+w+r = 8)
 #ifndef BB_CHUNK_GLOBAL
 #define BB_CHUNK_GLOBAL 8
 #endif
 constexpr int kChunkGlobal = BB_CHUNK_GLOBAL;  // key blocks per work item of a global row (equal to kChunk: equal-length items balance best)
-constexpr int kChunkMax = kChunkGlobal > kChunk ? kChunkGlobal : kChunk;
+constexpr int kChunkMax = kChunkGlobal > kSparseChunk ? kChunkGlobal : kSparseChunk;
 constexpr int kWaves = 2;     // one wave owns 32 query rows of the 64-row block
 constexpr int kThreads = 64 * kWaves;
 constexpr int kXcd = 8;       // accelerator dies; workgroup id modulo 8 selects the die
@@ -97,7 +98,7 @@ struct WorkItem {
   int bh;       // batch * H + head
   int j;        // query block
   int chunk;    // slice number: entries [chunk*len, (chunk+1)*len) of the row's key-block list,
-                // len = kChunkGlobal for a global row, kChunk otherwise
+                // len = kChunkGlobal for a global row, kSparseChunk otherwise
   int nchunks;  // slices this row is split into
   int slot;     // partial-result slot (valid when nchunks > 1)
   bool row_global;
@@ -117,7 +118,7 @@ inline RowSplit make_row_split(int BH, int nb, int g, int w, int r) {
   int sparse_ub = g + w + r;
   if (sparse_ub > nb) sparse_ub = nb;
   s.cg = (nb + kChunkGlobal - 1) / kChunkGlobal;
-  s.cs = (sparse_ub + kChunk - 1) / kChunk;
+  s.cs = (sparse_ub + kSparseChunk - 1) / kSparseChunk;
   if (s.cs < 1) s.cs = 1;
   s.items_per_bh = g * s.cg + (nb - g) * s.cs;
   s.slots_per_bh = (s.cg > 1 ? g * s.cg : 0) + (s.cs > 1 ? (nb - g) * s.cs : 0);
@@ -217,7 +218,7 @@ __device__ __forceinline__ int build_key_list_range(const Pattern& pat, const in
 __device__ __forceinline__ int build_key_list(const Pattern& pat, const int32_t* rand_idx, int r,
                                               const uint8_t* kmask, int n, int bi, int h, int j,
                                               bool row_global, int chunk, int* klist) {
-  const int len = row_global ? kChunkGlobal : kChunk;
+  const int len = row_global ? kChunkGlobal : kSparseChunk;
   return build_key_list_range(pat, rand_idx, r, kmask, n, bi, h, j, row_global, chunk * len, len, klist);
 }
 
