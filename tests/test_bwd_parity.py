@@ -179,3 +179,32 @@ def test_fp32_backward_is_refused_not_faked():
     with pytest.raises(bb.BigBirdError) as e:
         bb.bigbird_attn_bwd(Q, K, V, O, LSE, dO, empty, g=1, w=1, scale=0.125)
     assert e.value.status == -6
+
+
+def test_seeded_sweep_of_small_configurations():
+    """Twenty-five seeded combinations of batch, heads, length, pattern, placement and padding."""
+    rng = np.random.default_rng(20261)
+    done = 0
+    while done < 25:
+        nb = int(rng.integers(1, 17))
+        g = int(rng.integers(0, min(nb, 3) + 1))
+        w = int(rng.choice([1, 3, 5, 7]))
+        r = int(rng.integers(0, 5))
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        mode = int(rng.integers(0, 2))
+        n = nb * 64
+        try:
+            ridx = oracle.make_rand_idx(H, n, 64, g, w, r, int(rng.integers(0, 1000)), mode)
+        except ValueError:
+            continue
+        t = inp.make_tensors(B, H, n, 64, int(rng.integers(0, 10000)), "bf16", with_dO=True)
+        km = None
+        if rng.random() < 0.5:
+            km = np.ones((B, n), dtype=np.uint8)
+            for bi in range(B):
+                km[bi, int(rng.integers(0, n + 1)):] = 0
+                if rng.random() < 0.3:
+                    a = int(rng.integers(0, n)); km[bi, a:a + int(rng.integers(1, 130))] = 0
+        check_full(t, ridx, 64, g, w, 0.125, key_mask=km, mode=mode,
+                   tag=f"bwd sweep {done}: B{B} H{H} nb{nb} g{g} w{w} r{r} mode{mode} pad{km is not None}")
+        done += 1

@@ -238,3 +238,35 @@ def test_cfg2_lse_bound_holds_for_every_row():
     # outputs are convex combinations of V rows
     vmax = np.abs(t["V"]).max()
     assert np.abs(Oh).max() <= vmax + 1e-2
+
+
+def test_seeded_sweep_of_small_configurations():
+    """Forty seeded combinations of batch, heads, length, pattern, global placement, padding and
+    storage type (every legal corner the other tests do not name), each compared in full."""
+    rng = np.random.default_rng(20260)
+    done = 0
+    while done < 40:
+        nb = int(rng.integers(1, 21))
+        g = int(rng.integers(0, min(nb, 3) + 1))
+        w = int(rng.choice([1, 3, 5, 7]))
+        r = int(rng.integers(0, 5))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        mode = int(rng.integers(0, 2))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        n = nb * 64
+        try:
+            ridx = oracle.make_rand_idx(H, n, 64, g, w, r, int(rng.integers(0, 1000)), mode)
+        except ValueError:
+            continue  # fewer than r candidate blocks somewhere: not a legal pattern
+        t = inp.make_tensors(B, H, n, 64, int(rng.integers(0, 10000)), dtype)
+        km = None
+        if rng.random() < 0.5:
+            km = np.ones((B, n), dtype=np.uint8)
+            for bi in range(B):
+                km[bi, int(rng.integers(0, n + 1)):] = 0          # valid prefix of any length, 0 included
+                if rng.random() < 0.3:
+                    a = int(rng.integers(0, n)); km[bi, a:a + int(rng.integers(1, 130))] = 0   # a hole
+        scale = float(rng.choice([0.125, 0.2, 0.05]))
+        check_full(t, ridx, dtype, 64, g, w, scale, key_mask=km, mode=mode,
+                   tag=f"sweep {done}: B{B} H{H} nb{nb} g{g} w{w} r{r} mode{mode} {dtype} pad{km is not None}")
+        done += 1
