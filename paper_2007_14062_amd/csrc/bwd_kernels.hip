@@ -157,24 +157,14 @@ void bwd_dq_kernel(BwdParams p) {
     zero_acc(s);
     dp[0] = neg_d;
     dp[1] = neg_d;
-    {
-      bf16x8 ka[2][4];
-      so.read(kt, ka);
+    bf16x8 ka[2][4], va[2][4];
+    so.read(kt, ka);
+    so.read(vt, va);
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
+    for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
-          s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], s[t], 0, 0, 0);
-    }
-    {
-      bf16x8 va[2][4];
-      so.read(vt, va);
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-          dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t][ks], dob[ks], dp[t], 0, 0, 0);
-    }
+      for (int t = 0; t < 2; ++t)
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[t][ks], qb[ks], s[t], 0, 0, 0);
     if (vbits != ~0ull) {  // partly padded block: masked keys get probability 0
       const uint64_t mine = vbits >> (hf * 4);
 #pragma unroll
@@ -183,14 +173,31 @@ void bwd_dq_kernel(BwdParams p) {
         for (int r = 0; r < 16; ++r)
           if (!((mine >> (t * 32 + acc_row(r, 0))) & 1)) s[t][r] = neg_inf();
     }
-    // dS^T = P^T o (dP^T - D), P^T = 2^(S^T c - LSE log2e)
+    // P^T = 2^(S^T c - LSE log2e) on the vector ALU while the matrix pipe computes dP^T (the issue
+    // order "one MFMA, eight vector instructions" is pinned: left alone the compiler queues the
+    // MFMAs first, and the wave can issue nothing else meanwhile)
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[t][ks], dob[ks], dp[t], 0, 0, 0);
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float pv = fast_exp2(__builtin_fmaf(s[t][r], c, -lse2));
-        s[t][r] = pv * dp[t][r];
+        s[t][r] = fast_exp2(__builtin_fmaf(s[t][r], c, -lse2));
+        asm volatile("" : "+v"(s[t][r]));  // computed here, beside the MFMAs, not where it is used
       }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x402, 8, 0);
+    }
+    // dS^T = P^T o (dP^T - D)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[t][r] *= dp[t][r];
     bf16x8 dsb[4];
     pack_acc_bf16(s, dsb);
 
