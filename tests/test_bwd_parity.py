@@ -94,6 +94,21 @@ def test_summarisation_encoder_length_3072():
         assert max(errs) <= TOL, (h, errs)
 
 
+def test_long_sequence_one_head_in_full():
+    """n = 8192 (nb = 128): sixteen slices per global row and per global key column go through
+    the fixed-order reduction; one of the three heads is compared in full."""
+    B, H, n, g, w, r = 1, 3, 8192, 2, 3, 3
+    t = inp.make_tensors(B, H, n, 64, 91, "bf16", with_dO=True)
+    ridx = bb.bigbird_make_rand_idx(H, n, 64, g, w, r, 19)
+    dQ, dK, dV = run_fwd_bwd(t, ridx, g, w, 0.125)
+    h = 2
+    sub = {k: v[:, h:h + 1] for k, v in t.items() if k in ("Q", "K", "V", "dO")}
+    rQ, rK, rV = oracle.attn_bwd(sub["Q"], sub["K"], sub["V"], sub["dO"], ridx[h:h + 1], 64, g, w, 0.125)
+    errs = [np.abs(to_host(x)[:, h:h + 1] - r_).max() for x, r_ in ((dQ, rQ), (dK, rK), (dV, rV))]
+    print(f"bwd n=8192 head {h}: max|ddQ|={errs[0]:.3e} max|ddK|={errs[1]:.3e} max|ddV|={errs[2]:.3e}")
+    assert max(errs) <= TOL, errs
+
+
 def test_single_block_sequence():
     t = inp.make_tensors(2, 1, 64, 64, 20, "bf16", with_dO=True)
     empty = np.full((1, 1, 0), -1, dtype=np.int32)

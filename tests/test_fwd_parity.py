@@ -218,6 +218,13 @@ def test_cfg5_long_sequence_sampled_rows():
     _sampled_parity(inp.WORKLOADS["cfg5_long_seq"], n_bh=2)
 
 
+def test_maximum_length_sampled_rows():
+    """n = 65 536 (nb = 1024, the longest sequence the backward accepts): sixteen workgroups and
+    a merge per global row, key lists built from a 3072-entry table row set; sampled rows."""
+    wl = inp.Workload("max_len", B=1, H=2, n=65536, pattern_seed=21, data_seed=321)
+    _sampled_parity(wl, n_bh=1)
+
+
 def test_cfg2_lse_bound_holds_for_every_row():
     """A property that holds at any size: sum_k exp(S_ik - LSE_i) = 1 implies
     max_k S_ik <= LSE_i <= max_k S_ik + ln|N(i)|; checked here through the Q = 0-free route
