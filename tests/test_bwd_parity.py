@@ -184,6 +184,32 @@ def test_cfg4_sampled_heads():
     assert np.abs(qdq - kdk).max() <= 1e-3 * max(1.0, np.abs(qdq).max()) + 0.5
 
 
+def test_cfg3_shape_backward_with_padding_sampled_heads():
+    """The key-padding workload (B = 8, lengths 1024..4096) through forward + backward; the
+    oracle is run on three (batch, head) slices, among them the shortest and the longest row."""
+    wl = inp.WORKLOADS["cfg3_key_padding"]
+    t = inp.make_tensors(wl.B, wl.H, wl.n, wl.d, wl.data_seed, "bf16", with_dO=True)
+    km = inp.lengths_to_key_mask(inp.make_valid_lengths(wl.B, wl.n, wl.b, wl.length_seed), wl.n)
+    ridx = bb.bigbird_make_rand_idx(wl.H, wl.n, wl.b, wl.g, wl.w, wl.r, wl.pattern_seed)
+    dQ, dK, dV = run_fwd_bwd(t, ridx, wl.g, wl.w, wl.scale, key_mask=km)
+    hQ, hK, hV = to_host(dQ), to_host(dK), to_host(dV)
+    assert np.isfinite(hQ).all() and np.isfinite(hK).all() and np.isfinite(hV).all()
+    lens = km.sum(axis=1)
+    worst = 0.0
+    for (bi, h) in [(int(lens.argmin()), 0), (int(lens.argmax()), 7), (3, 11)]:
+        sl = (slice(bi, bi + 1), slice(h, h + 1))
+        rQ, rK, rV = oracle.attn_bwd(t["Q"][sl], t["K"][sl], t["V"][sl], t["dO"][sl], ridx[h:h + 1],
+                                     wl.b, wl.g, wl.w, wl.scale, key_mask=km[bi:bi + 1])
+        errs = [np.abs(hQ[sl] - rQ).max(), np.abs(hK[sl] - rK).max(), np.abs(hV[sl] - rV).max()]
+        print(f"cfg3 bwd (b={bi}, len={int(lens[bi])}, h={h}): max|ddQ|={errs[0]:.3e} max|ddK|={errs[1]:.3e} "
+              f"max|ddV|={errs[2]:.3e}")
+        worst = max(worst, *errs)
+    assert worst <= TOL
+    pad = km == 0
+    for bi in range(wl.B):   # gradients of padded keys are exactly zero
+        assert (hK[bi][:, pad[bi]] == 0).all() and (hV[bi][:, pad[bi]] == 0).all()
+
+
 def test_fp32_backward_is_refused_not_faked():
     torch = torch_mod()
     t = inp.make_tensors(1, 1, 128, 64, 24, "f32", with_dO=True)
