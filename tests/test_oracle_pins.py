@@ -175,6 +175,75 @@ def test_rand_idx_properties_and_determinism():
         make_rand_idx(1, 5 * 64, 64, 2, 3, 3, seed=0)     # block 2 has no candidate left
 
 
+def test_rand_idx_leading_globals_properties():
+    """The App. D wording ("the first g blocks are global"): same rules, other global set, checked by
+    an inline loop that uses nothing from the oracle but the table."""
+    H, n, b, g, w, r = 2, 1536, 64, 3, 5, 2
+    nb = n // b
+    t = make_rand_idx(H, n, b, g, w, r, seed=8, global_mode=GLOBAL_LEADING)
+    assert t.dtype == np.int32 and t.shape == (H, nb, r)
+    picked = np.zeros(nb, dtype=np.int64)
+    for h in range(H):
+        for j in range(nb):
+            row = [int(x) for x in t[h, j]]
+            if j < g:                                  # blocks 0 .. g-1 are the global ones
+                assert row == [-1] * r
+                continue
+            assert row == sorted(row) and len(set(row)) == r
+            for k in row:
+                assert g <= k < nb                     # never a global block
+                assert abs(k - j) > (w - 1) // 2       # never inside the window
+                picked[k] += 1
+    assert picked[nb - 1] > 0                          # the last block is an ordinary one here
+    assert (make_rand_idx(H, n, b, g, w, r, seed=8, global_mode=GLOBAL_LEADING) == t).all()
+    assert (make_rand_idx(H, n, b, g, w, r, seed=8, global_mode=GLOBAL_FIRST_LAST) != t).any()
+    assert validate_rand_idx(t, H, n, b, g, w, r, GLOBAL_LEADING)
+    assert not validate_rand_idx(t, H, n, b, g, w, r, GLOBAL_FIRST_LAST)   # nb-1 is global there
+
+
+def test_count_block_pairs_by_double_loop_and_closed_forms():
+    """count_block_pairs, with and without a key-block validity vector, against (i) a double loop over
+    (j, k) written from the three set definitions (Sec. 2 globals, App. D window and random
+    blocks), (ii) the closed form P(nb) = 10 nb - 18 for g/w/r = 2/3/3 and (iii), for a valid prefix
+    of L blocks, the count derived by hand below."""
+    H, n, b, g, w, r = 3, 2048, 64, 2, 3, 3
+    nb = n // b
+    t = make_rand_idx(H, n, b, g, w, r, seed=12)
+
+    def loop_count(valid):
+        total = 0
+        for h in range(H):
+            for j in range(nb):
+                for k in range(nb):
+                    is_g_row = j == 0 or j == nb - 1
+                    is_g_col = k == 0 or k == nb - 1
+                    in_win = abs(k - j) <= 1
+                    in_rnd = any(int(x) == k for x in t[h, j])
+                    if (is_g_row or is_g_col or in_win or in_rnd) and valid[k]:
+                        total += 1
+        return total
+
+    all_valid = np.ones(nb, dtype=bool)
+    assert count_block_pairs(t, n, b, g, w) == loop_count(all_valid) == H * (10 * nb - 18)
+    rng = np.random.default_rng(3)
+    for _ in range(4):
+        valid = rng.random(nb) < 0.6
+        assert count_block_pairs(t, n, b, g, w, key_block_valid=valid) == loop_count(valid)
+    # Valid prefix of L blocks, 2 <= L <= nb - 2 (the last global block is padded).  Per head:
+    #   the two global rows see L valid blocks each;
+    #   every other row sees block 0;
+    #   window: rows 1 .. L-1 see themselves (L-1 pairs), rows 2 .. L see j-1 with j-1 >= 1
+    #   (L-1 pairs), rows 1 .. L-2 see j+1 <= L-1 (L-2 pairs); block 0 as a window block of row 1
+    #   is the global pair already counted;
+    #   random: counted from the table (entries < L), they never coincide with the above.
+    for L in (2, 5, 17, nb - 2):
+        valid = np.arange(nb) < L
+        rand_pairs = sum(int(0 <= int(x) < L) for h in range(H) for j in range(1, nb - 1) for x in t[h, j])
+        by_hand = H * (2 * L + (nb - 2) + (L - 1) + (L - 1) + (L - 2)) + rand_pairs
+        assert count_block_pairs(t, n, b, g, w, key_block_valid=valid) == by_hand
+        assert loop_count(valid) == by_hand
+
+
 def test_rand_idx_uniform_over_candidates():
     """Chi-square of picks over the candidate blocks of one row, across many heads."""
     H, n, b, g, w, r = 4000, 16 * 64, 64, 2, 3, 3
