@@ -145,6 +145,21 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
       }
     }
     q.g_wgs = g * q.ng;
+    {
+      // Persistent workgroups: as many as stay resident beside the global-row workgroups (a die
+      // holds 64 workgroups of this kernel: two per CU), at most one wave per item.
+      const int slots_per_die = 64;
+      const int n_global = q.bh_rounds * q.g_wgs;
+      const int want = (q.bh_rounds * q.n_sitems + 3) / 4;
+      int avail = slots_per_die - n_global;
+      if (avail < 16) avail = 32;  // the global rows alone fill the die: queue behind them
+      q.p_wgs = want < avail ? want : avail;
+      // a wave lists the items it has to redo by the exact recurrence in one register, a lane per
+      // item: no wave may be given more than 64 items, whatever that does to residency
+      const int per_wave_cap = 64;
+      const int floor_wgs = (q.bh_rounds * q.n_sitems + 4 * per_wave_cap - 1) / (4 * per_wave_cap);
+      if (q.p_wgs < floor_wgs) q.p_wgs = floor_wgs;
+    }
     p.cmb_g_rows = q.ng > 1 ? g : 0;
     p.cmb_g_n = q.ng;
     p.cmb_s_rows = q.cs > 1 ? p.nb - g : 0;

@@ -1,38 +1,54 @@
 // bf16 forward kernel: the tuned path of the BERT-shaped workloads.
 //
 // Same mathematics as the fp32 kernel (eq. (AT) per head on the App. D pattern),
-// organised around what limits it on this chip at d = 64: the vector ALU (one
-// exponential per score), the LDS port and the matrix pipe are all within a factor of
-// two of each other, so every vector instruction per score counts.
-//   * One wavefront owns one work item: a 64-query block against a slice of its key
-//     blocks.  Waves never wait for each other inside the key-block loop.  A workgroup
-//     is four such waves: either four consecutive non-global query blocks (independent
-//     items), or one global query block whose key list is dealt out 16 blocks per wave
-//     and merged in LDS at the end (no partial results in HBM, no second kernel, for
-//     up to 64 key blocks; longer rows take several workgroups plus the merge kernel).
-//   * Softmax without a running maximum.  The query fragments are multiplied by
-//     scale*log2(e) once per item (and rounded to bf16 again), so a score leaves the MFMA
-//     as the base-2 exponent and a probability is one v_exp_f32: no multiply-add, no row
-//     maximum, no accumulator rescale.  Softmax is shift invariant and fp32/bf16 carry
-//     eight exponent bits, so a fixed reference of 0 is exact as long as the row sum stays
-//     inside [2^-40, 2^60]; a wave checks that at the end of its item and, if a row left
-//     the range (logits beyond about +-28 in natural units), recomputes the item with the
-//     classical running-maximum recurrence (slow_item).  Both paths give the same
-//     un-normalised (reference, sum, O~) triple to the common epilogue.
+// organised around what limits it on this chip at d = 64: the vector port (one
+// exponential per score) and the matrix pipe are within a few percent of each other,
+// so every vector instruction per score counts.
+//   * One wavefront owns one work item at a time: a 64-query block against a slice of
+//     its key blocks (up to 16).  Waves never wait for each other inside the key-block
+//     loop.  Per die, the first workgroups take one global query block each (key list
+//     dealt out 16 blocks per wave, the four waves' results merged in LDS: no partial
+//     results in HBM and no second kernel for up to 64 key blocks; longer rows take
+//     several workgroups plus the merge kernel).  The other workgroups stay for the whole
+//     launch: their waves share out the die's non-global items round robin and run them
+//     as one uninterrupted stream of block pairs -- the next item's query tile and first
+//     K tile ride at the end of this item's K and V tile streams, so the matrix pipe
+//     only idles for the item's output.
+//   * Softmax without a running maximum.  A probability is 2^(score * scale*log2(e)): one
+//     multiplication and one v_exp_f32 per score, no row maximum, no accumulator rescale.
+//     Softmax is shift invariant and fp32/bf16 carry eight exponent bits, so a fixed
+//     reference of 0 is exact as long as the row sum stays inside [2^-40, 2^60]; a wave
+//     checks that at the end of its item and, if a row left the range (logits beyond about
+//     +-28 in natural units), puts the item on a list that it works off afterwards with the
+//     classical running-maximum recurrence (slow_item), as it does with items that have
+//     padded keys inside a block.  Both paths give the same un-normalised (reference, sum,
+//     O~) triple to the common epilogue.  (Folding the factor into the query operand would
+//     save the multiplication, but the operand would have to be rounded to bf16 again: that
+//     perturbs a logit by up to 2^-9 of its size, four times the error of everything else in
+//     LSE, and the backward pass, which recomputes the logits exactly, then sees rows whose
+//     probabilities do not sum to one -- measured: gradient errors three times as large.)
+//   * Row sums come from the matrix pipe as well: one small MFMA per 16 keys multiplies
+//     the probabilities (already in operand layout) by a matrix of ones and zeros
+//     (RowSumOperand).  That takes sixteen additions per unit off the vector port.
 //   * The block pair is cut into four units (32 keys x 32 queries each) that flow through
 //     a three-stage software pipeline inside the wave: scores of unit u+1 on the matrix
 //     pipe, exponentials of unit u on the vector ALU, P V of unit u-1 on the matrix pipe
-//     again.  The pipeline runs across key-block boundaries; its first and last pairs
-//     are separate instantiations, so every loop body is straight-line code whose issue
-//     order (one MFMA, four vector instructions, ...) is pinned with scheduling group
-//     barriers.  Every K and V^T operand fetched from LDS feeds two MFMAs (two query
-//     tiles), which halves the LDS traffic per flop.
+//     again.  The pipeline runs across key-block and item boundaries with one
+//     straight-line body (pair_step) whose issue order (one MFMA, two exponentials, a
+//     conversion, ...) is pinned with scheduling group barriers.  Every K and V^T operand
+//     fetched from LDS feeds two MFMAs (two query tiles), which halves the LDS traffic
+//     per flop.
 //   * K and V tiles go global -> LDS directly (no registers in between), one 8 KB
 //     buffer each, handled as 32-key halves: as soon as a half has been read out into
 //     operand registers the same half of the next key block is requested, so a load has
 //     three quarters of a block pair to land.
 //   * V^T operands come from the transposing LDS read; the LDS layout is swizzled so
 //     that neither read pattern has bank conflicts.
+//   * The two waves of a SIMD get their issue priority from the pairs they still have to
+//     do, so that they finish together (set_issue_priority).
+// -DBB_STAMPS builds a development variant that writes per-wave time stamps into the
+// partial-result workspace (which must then hold 128 bytes per wave of the launch); the
+// library proper is built without it.
 #include "fwd_epilogue.h"
 #include "tile_ops.h"
 
@@ -58,6 +74,7 @@ __device__ __forceinline__ void zero_acc(f32x16 (&a)[2]) {
     for (int r = 0; r < 16; ++r) a[t][r] = 0.f;
 }
 
+
 __device__ __forceinline__ const char* uniform_ptr(const char* p) {
   const uintptr_t v = reinterpret_cast<uintptr_t>(p);
   const unsigned lo = __builtin_amdgcn_readfirstlane(static_cast<unsigned>(v));
@@ -72,11 +89,13 @@ __device__ __forceinline__ const char* uniform_ptr(const char* p) {
 // l/8 and on the parity of ii: voff[0] / voff[1] are the per-lane byte offsets for even /
 // odd ii.  The instruction's immediate offset moves the global and the LDS address alike,
 // so the four instructions share one base pair (M0, scalar address).
-__device__ __forceinline__ void half_load_async(const char* gtile, unsigned lds, int hh,
+__device__ __forceinline__ void half_load_async(const char* gtile_, unsigned lds, int hh,
                                                 const unsigned (&voff)[2]) {
+  const char* gtile = uniform_ptr(gtile_);  // wave uniform by construction: it has to sit in scalar registers
   asm volatile(
       "s_mov_b32 m0, %3\n\t"
-      "s_nop 0\n\t"  // a scalar write of M0 needs one wait state before an LDS-DMA load reads it
+      "s_nop 4\n\t"  // wait states the compiler cannot see to from outside: M0 written by a scalar instruction (1) and an
+                       // address register pair that a vector instruction (v_readlane) may just have written (5)
       "global_load_lds_dwordx4 %0, %2\n\t"
       "global_load_lds_dwordx4 %1, %2 offset:1024\n\t"
       "global_load_lds_dwordx4 %0, %2 offset:2048\n\t"
@@ -93,33 +112,13 @@ __device__ __forceinline__ void tile_load_async_wave(const char* gtile_, unsigne
   half_load_async(gtile, lds, 1, voff);
 }
 
-// One entry of a pattern-table row per lane, requested ahead of a whole tile (global -> LDS as in
-// half_load_async) and waited for while the tile's eight loads stay in flight: loads return in
-// order, so "all but the eight youngest" is exactly the table entry.  Request, tile loads and wait
-// sit in one asm statement: the compiler sees the register only once the value is in it.
-__device__ __forceinline__ int table_entry_then_tile(const int32_t* entry, const char* gtile_, unsigned lds,
-                                                     const unsigned (&voff)[2]) {
-  const char* gtile = uniform_ptr(gtile_);
-  int e;
-  asm volatile(
-      "global_load_dword %0, %1, off\n\t"
-      "s_mov_b32 m0, %5\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %2, %4\n\t"
-      "global_load_lds_dwordx4 %3, %4 offset:1024\n\t"
-      "global_load_lds_dwordx4 %2, %4 offset:2048\n\t"
-      "global_load_lds_dwordx4 %3, %4 offset:3072\n\t"
-      "s_mov_b32 m0, %7\n\t"
-      "s_nop 0\n\t"
-      "global_load_lds_dwordx4 %2, %6\n\t"
-      "global_load_lds_dwordx4 %3, %6 offset:1024\n\t"
-      "global_load_lds_dwordx4 %2, %6 offset:2048\n\t"
-      "global_load_lds_dwordx4 %3, %6 offset:3072\n\t"
-      "s_waitcnt vmcnt(8)"
-      : "=&v"(e)
-      : "v"(entry), "v"(voff[0]), "v"(voff[1]), "s"(gtile), "s"(lds), "s"(gtile + kHalfTile), "s"(lds + kHalfTile)
-      : "memory");
-  return e;
+// The lane number again, as a value the compiler cannot trace back.  Addresses and masks computed
+// from it are then computed where they are used; computed from the known lane number they would
+// be hoisted out of the item loop and carried through the pair loop, which has no register to
+// spare (spilled, they come back one scratch load and one full memory wait at a time).
+__device__ __forceinline__ int lane_again(int lane) {
+  asm volatile("" : "+v"(lane));
+  return lane;
 }
 
 // Waits and compiler fences.  The tile loads are invisible to the compiler's wait-count
@@ -133,6 +132,23 @@ __device__ __forceinline__ void wait_tile_loads() {
 __device__ __forceinline__ void wait_lds_reads() {
   __builtin_amdgcn_s_waitcnt(kLgkmcnt0);
   asm volatile("" ::: "memory");
+}
+
+// Issue priority of the wave by the block pairs it still has to do, in steps of four pairs: the
+// two waves of a SIMD would otherwise be served oldest first, the older one would finish pairs
+// ahead of the younger, and the younger would do its last pairs alone at a little more than half
+// the throughput the SIMD has with two waves.  (Priority is an immediate operand.)
+__device__ __forceinline__ void set_issue_priority(int remaining_pairs) {
+  const int pr = remaining_pairs >> 2;
+  if (pr >= 3) {
+    __builtin_amdgcn_s_setprio(3);
+  } else if (pr == 2) {
+    __builtin_amdgcn_s_setprio(2);
+  } else if (pr == 1) {
+    __builtin_amdgcn_s_setprio(1);
+  } else {
+    __builtin_amdgcn_s_setprio(0);
+  }
 }
 
 // Key-block list of a non-global row without a padding mask, from the row of the pattern table
@@ -175,8 +191,9 @@ __device__ __forceinline__ int finish_key_list_sparse(const Pattern& pat, int r,
 // A block pair (64 queries x 64 keys) is four units u = (t, q): keys 32t .. 32t+31 against the
 // query tile q (A: queries 0..31, B: 32..63), taken in the order (0,A) (0,B) (1,A) (1,B).
 // Stage S(u): 4 MFMAs, S^T = K_t Q_q^T (keys along MFMA rows, a lane owns one query column).
-// Stage E(u): 16 exponentials, 8 conversions to bf16 pairs, 8 packed dots for the row sum.
-// Stage P(u): 4 MFMAs, O_q^T += V_t^T P^T, the converted scores being the B operand as they are.
+// Stage E(u): 16 exponentials, 8 conversions to bf16 pairs.
+// Stage P(u): 4 MFMAs, O_q^T += V_t^T P^T, the converted scores being the B operand as they are,
+//             and 2 small MFMAs for the row sums.
 // Slot k of the stream issues S(k+1), E(k), P(k-1).  Unit (0,A) of the next pair is therefore
 // started in the last slot of this one, and P of unit (1,B) is finished in the first slot of
 // the next pair (`sA`, `p3` carry them across).
@@ -186,17 +203,14 @@ __device__ __forceinline__ int finish_key_list_sparse(const Pattern& pat, int r,
 // was requested three slots earlier; the request for the half after that follows as soon as the
 // read has returned.  Tile loads outstanding at the start of a pair, oldest first:
 // K(i+1).t0 and V(i).t1 (8 instructions).
-//   FIRST: no pair precedes (nothing to finish for it).
-//   TAIL : 0 = at least two more pairs follow, 1 = exactly one, 2 = none.
 // Blocks with padded keys inside never come here: such items take the slow path.
 struct PairCtx {
-  const char* kbase;   // K, V of this (batch, head)
-  const char* vbase;
   const char* lds_k;   // this wave's K and V tile buffers
   const char* lds_v;
   unsigned lds_k_a, lds_v_a;  // the same as LDS byte addresses (scalar)
   unsigned voff[2];
   int hf;
+  float c;  // scale * log2(e)
 };
 
 __device__ __forceinline__ void read_k_half(const StraightOffsets& so, const char* tile, int t, bf16x8 (&f)[4]) {
@@ -221,6 +235,25 @@ __device__ __forceinline__ void unit_scores(const bf16x8 (&k)[4], const bf16x8 (
   for (int ks = 1; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k[ks], q[ks], s, 0, 0, 0);
 }
 
+// Row sums on the matrix pipe.  A B operand of the 32x32x16 product (lane: query lane % 32, eight
+// keys chosen by lane / 32) is read by the 16x16x32 product as column lane % 16, key group
+// lane / 16: groups 0 and 2 of column c are the two key halves of query c, groups 1 and 3 those of
+// query c + 16.  With an A operand whose row m is one on the groups g with m + g even and zero on
+// the others, even output rows hold the sums of queries 0..15 and odd rows those of queries
+// 16..31, and the output layout (lane: column lane % 16, rows 4 (lane / 16) .. + 3) gives every lane
+// the total of its own query: element 0 for lane % 32 < 16, element 1 otherwise.  The sums are
+// those of the rounded probabilities, the same numbers that multiply V.
+struct RowSumOperand {
+  bf16x8 a;
+  __device__ __forceinline__ explicit RowSumOperand(int lane) {
+    const __bf16 v = static_cast<__bf16>((((lane & 15) + (lane >> 4)) & 1) ? 0.f : 1.f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a[e] = v;
+  }
+};
+__device__ __forceinline__ float row_total(const f32x4& ls, int col) { return col < 16 ? ls[0] : ls[1]; }
+
+// O^T += V_t^T P^T for one unit.
 __device__ __forceinline__ void unit_pv(const bf16x8 (&v)[2][2], const bf16x8 (&pb)[2], f32x16 (&o)[2]) {
 #pragma unroll
   for (int sgl = 0; sgl < 2; ++sgl)
@@ -229,28 +262,39 @@ __device__ __forceinline__ void unit_pv(const bf16x8 (&v)[2][2], const bf16x8 (&
       o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[dt][sgl], pb[sgl], o[dt], 0, 0, 0);
 }
 
-// Probabilities of one unit as two B operands (16 keys each).  This lane's share of the row sum
-// is taken from the unrounded values with plain additions, two chains: the packed bf16 dot
-// instruction would halve the count, but it runs on the matrix pipe's data path and stalls
-// against the MFMAs in flight (measured: 16 cycles per dot beside MFMAs, 4 per addition).
-__device__ __forceinline__ void unit_probs(const f32x16& s, bf16x8 (&pb)[2], float (&l_run)[2]) {
+// The same, and the unit's share of the row sums.
+__device__ __forceinline__ void unit_pv(const bf16x8 (&v)[2][2], const bf16x8 (&pb)[2], f32x16 (&o)[2],
+                                        const RowSumOperand& ones, f32x4& ls) {
+#pragma unroll
+  for (int sgl = 0; sgl < 2; ++sgl) {
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+      o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[dt][sgl], pb[sgl], o[dt], 0, 0, 0);
+    ls = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones.a, pb[sgl], ls, 0, 0, 0);
+  }
+}
+
+// Probabilities of one unit as two B operands (16 keys each).  (The row sums are taken from these
+// operands by unit_pv: sixteen additions per unit here, or eight packed bf16 dots -- which stall
+// against the MFMAs in flight, measured 16 cycles each -- would sit on the vector port, which is
+// the busier of the two pipes.)
+__device__ __forceinline__ void unit_probs(const f32x16& s, float c, bf16x8 (&pb)[2]) {
 #pragma unroll
   for (int sgl = 0; sgl < 2; ++sgl)
 #pragma unroll
     for (int kk = 0; kk < 8; kk += 2) {
       const int r = sgl * 8 + kk;
-      const float p0 = fast_exp2(s[r]);
-      const float p1 = fast_exp2(s[r + 1]);
+      const float p0 = fast_exp2(s[r] * c);
+      const float p1 = fast_exp2(s[r + 1] * c);
       const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
       pb[sgl][kk] = pk[0];
       pb[sgl][kk + 1] = pk[1];
-      l_run[0] += p0;
-      l_run[1] += p1;
     }
 }
 
-// issue order of one slot: eight times (one MFMA, [LDS reads,] four vector instructions); nothing
-// moves across the end of a slot
+// issue order of one slot: eight times (one MFMA, [LDS reads,] two exponentials, their
+// conversion), the two small row-sum MFMAs after the fourth and the eighth; nothing moves across
+// the end of a slot
 template <int DS_READS>
 __device__ __forceinline__ void pin_slot() {
 #pragma unroll
@@ -258,93 +302,334 @@ __device__ __forceinline__ void pin_slot() {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     if (u * 2 < DS_READS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // two exponentials
-    __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);  // their conversion and row-sum steps
+    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // the next two scalings, a conversion, a lane read for a tile address
+    if (u == 3 || u == 7) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
   }
   __builtin_amdgcn_sched_barrier(0);
 }
 
-#ifdef BB_EXP_NOLOAD
-#define half_load_async(...) ((void)0)
-#define wait_tile_loads wait_nothing
-template <int N> __device__ __forceinline__ void wait_nothing() {}
-#endif
-#ifdef BB_EXP_NOWAIT
-#define wait_tile_loads wait_nothing
-template <int N> __device__ __forceinline__ void wait_nothing() {}
-#endif
-// One block pair.  more1 / more2: one / two further pairs follow in this item (wave uniform).
-// The arithmetic is the same for every pair of an item, so that one straight-line body serves
-// them all: the first pair finishes a predecessor that does not exist (p3 = 0 on entry, V
-// fragments zeroed), the last one starts a successor that does not exist (scores of stale K
-// fragments, never used) -- eight idle MFMAs per item instead of six differently scheduled
-// copies of the body.  Only the tile requests and the counts waited for depend on what follows;
-// they sit at the slot boundaries behind scalar branches.
+// One block pair.  The arithmetic and the memory requests are the same for every pair, so that
+// one straight-line body serves them all: the first pair of an item finishes a predecessor that
+// does not exist (p3 = 0 on entry, V fragments zeroed), the last one starts a successor that does
+// not exist (scores of whatever the K fragments hold, never used) -- eight idle MFMAs per item
+// instead of differently scheduled copies of the body -- and a stream that has run out of tiles
+// delivers a tile nobody uses (see TileStreams).
+// k1 / v1: global address of the tile that follows this pair's in the K / V stream; k2: the one
+// after that in the K stream.
 __device__ __forceinline__ void pair_step(const PairCtx& cx, const StraightOffsets& so, const TransposedOffsets& to,
                                           const bf16x8 (&qb)[2][4], bf16x8 (&ka)[2][4], bf16x8 (&va)[2][2][2],
-                                          f32x16& sA, bf16x8 (&p3)[2], f32x16 (&o)[2][2], float (&l_run)[2][2],
-                                          bool more1, bool more2, size_t off1, size_t off2) {
+                                          f32x16& sA, bf16x8 (&p3)[2], f32x16 (&o)[2][2],
+                                          const RowSumOperand& ones, f32x4 (&ls)[2],
+                                          const char* k1, const char* v1, const char* k2) {
   f32x16 sB, sC, sD;
   bf16x8 p0[2], p1[2], p2[2];
 
   // ---- slot 0: the reads issued in the previous slot (K.t1, V.t0 of this pair) have returned
   wait_lds_reads();
-  if (more1) {
-    half_load_async(cx.kbase + off1, cx.lds_k_a, 1, cx.voff);
-    half_load_async(cx.vbase + off1, cx.lds_v_a, 0, cx.voff);
-  }
+  half_load_async(k1, cx.lds_k_a, 1, cx.voff);
+  half_load_async(v1, cx.lds_v_a, 0, cx.voff);
   unit_scores(ka[0], qb[1], sB);
-  unit_pv(va[1], p3, o[1]);
-  unit_probs(sA, p0, l_run[0]);
+  unit_pv(va[1], p3, o[1], ones, ls[1]);
+  unit_probs(sA, cx.c, p0);
   pin_slot<0>();
 
   // ---- slot 1: K(i+1).t0 and V(i).t1 have landed
-  if (more1) wait_tile_loads<8>(); else wait_tile_loads<0>();
+  wait_tile_loads<8>();
   read_k_half(so, cx.lds_k, 0, ka[0]);
   read_v_half(to, cx.lds_v, 1, va[1]);
   unit_scores(ka[1], qb[0], sC);
-  unit_pv(va[0], p0, o[0]);
-  unit_probs(sB, p1, l_run[1]);
+  unit_pv(va[0], p0, o[0], ones, ls[0]);
+  unit_probs(sB, cx.c, p1);
   pin_slot<12>();
 
   // ---- slot 2
   wait_lds_reads();
-  if (more2) half_load_async(cx.kbase + off2, cx.lds_k_a, 0, cx.voff);
-  if (more1) half_load_async(cx.vbase + off1, cx.lds_v_a, 1, cx.voff);
+  half_load_async(k2, cx.lds_k_a, 0, cx.voff);
+  half_load_async(v1, cx.lds_v_a, 1, cx.voff);
   unit_scores(ka[1], qb[1], sD);
-  unit_pv(va[0], p1, o[1]);
-  unit_probs(sC, p2, l_run[0]);
+  unit_pv(va[0], p1, o[1], ones, ls[1]);
+  unit_probs(sC, cx.c, p2);
   pin_slot<0>();
 
   // ---- slot 3: K(i+1).t1 and V(i+1).t0 have landed
-  if (more2) wait_tile_loads<8>(); else if (more1) wait_tile_loads<4>();
+  wait_tile_loads<8>();
   read_k_half(so, cx.lds_k, 1, ka[1]);
   read_v_half(to, cx.lds_v, 0, va[0]);
   unit_scores(ka[0], qb[0], sA);
-  unit_pv(va[1], p2, o[0]);
-  unit_probs(sD, p3, l_run[1]);
+  unit_pv(va[1], p2, o[0], ones, ls[0]);
+  unit_probs(sD, cx.c, p3);
   pin_slot<12>();
 }
 
-#ifdef BB_EXP_NOLOAD
-#undef half_load_async
-#undef wait_tile_loads
-#endif
-#ifdef BB_EXP_NOWAIT
-#undef wait_tile_loads
-#endif
-#ifdef BB_EXP_NOLDS
-#undef read_k_half
-#undef read_v_half
-#endif
-// The item's block pairs through the pipeline.  On entry: K(0) is in the K buffer, V(0).t0 in
-// flight or landed (4 loads, the oldest outstanding), nothing else outstanding.
+// LDS of a workgroup (at namespace scope: the cold paths below are separate functions).
+__shared__ __attribute__((aligned(1024))) char lds_all[kFwdWaves][2 * kTile];  // per wave: K tile, V tile
+__shared__ int klist_all[kFwdWaves][kGlobalWaveLen];
+__shared__ float mrg_m[kFwdWaves][kBlk], mrg_l[kFwdWaves][kBlk];  // global rows: per-wave exponent, sum
+
+// What a wave knows about itself and its LDS.
+struct WaveCtx {
+  int lane, wv, hf, col;
+  char* lds_kv;  // this wave's 16 KB: K buffer, then V buffer
+  char* lds_k;
+  char* lds_v;
+  int* klist;
+  PairCtx cx;
+  __device__ __forceinline__ explicit WaveCtx(float c) {
+    lane = lane_id();
+    wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, and the compiler should know
+    hf = lane >> 5;
+    col = lane & 31;
+    lds_kv = lds_all[wv];
+    lds_k = lds_kv;
+    lds_v = lds_kv + kTile;
+    klist = klist_all[wv];
+    cx.lds_k = lds_k;
+    cx.lds_v = lds_v;
+    cx.hf = hf;
+    cx.c = c;
+#pragma unroll
+    for (int par = 0; par < 2; ++par) {
+      const int row = par * 8 + (lane >> 3);
+      cx.voff[par] = (lane >> 3) * 128 + (((lane & 7) ^ tile_swizzle(row)) << 4);
+    }
+    cx.lds_k_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_k));
+    cx.lds_v_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_v));
+  }
+};
+
+// Workgroup id -> work.  id % 8 is the die (XCD) the hardware dispatches to; each die gets
+// whole (batch, head) slices so that a slice's K and V stay in its L2.  The first workgroups
+// of a die take one global query block each (the longest items: 16 key blocks per wave).
+// The others stay for the whole launch: wave w of the die's persistent waves takes the
+// non-global items w, w + wave_stride, ... of the die, in (slice, query block) order, so that
+// all waves start at once and nearly all end together.
+struct Sched {
+  int xcd;
+  unsigned wg;        // workgroup number inside the die
+  unsigned n_gpart;   // global-row workgroups of the die
+  bool global_wg;
+  int n_items_die;    // non-global items of the die
+  int wave_stride;    // persistent waves of the die
+  __device__ __forceinline__ explicit Sched(const FwdParams& p) {
+    xcd = blockIdx.x % kXcd;
+    wg = blockIdx.x / kXcd;
+    n_gpart = static_cast<unsigned>(p.geo.bh_rounds) * p.geo.g_wgs;
+    global_wg = wg < n_gpart;
+    const int n_bh_die = xcd < p.BH ? (p.BH - xcd + kXcd - 1) / kXcd : 0;
+    n_items_die = n_bh_die * p.geo.n_sitems;
+    wave_stride = p.geo.p_wgs * kFwdWaves;
+  }
+};
+
+// One work item as the kernel sees it between its phases.
+struct Item {
+  int bh, j;           // (batch, head) slice and query block
+  int chunk, nchunks;  // slice of the row's key-block list, and how many there are
+  int slot;            // partial-result slot (nchunks > 1)
+  int cnt;             // key blocks in this slice
+  int kl;              // the list: lane t holds entry t % 16
+  bool any_partial;    // some listed block has padded keys inside
+};
+
+// Global addresses of an item's tiles (wave uniform, scalar arithmetic).
+struct ItemTiles {
+  const char* kbase;
+  const char* vbase;
+  const char* qtile;
+  int kl;
+  __device__ __forceinline__ ItemTiles(const FwdParams& p, const Item& it) {
+    const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
+    kbase = static_cast<const char*>(p.K) + bh_row0 * (kDim * 2);
+    vbase = static_cast<const char*>(p.V) + bh_row0 * (kDim * 2);
+    qtile = static_cast<const char*>(p.Q) + (bh_row0 + it.j * kBlk) * (kDim * 2);
+    kl = it.kl;
+  }
+  __device__ __forceinline__ const char* ktile(int i) const {
+    return kbase + static_cast<size_t>(__builtin_amdgcn_readlane(kl, i)) * kTile;
+  }
+  __device__ __forceinline__ const char* vtile(int i) const {
+    return vbase + static_cast<size_t>(__builtin_amdgcn_readlane(kl, i)) * kTile;
+  }
+};
+
+// Up to four entries of a pattern-table row through the scalar data path: request and wait sit
+// in one asm statement (the compiler sees the registers only once the values are in them), and
+// the wait is on the scalar/LDS counter, which the tile loads in flight do not touch.
+__device__ __forceinline__ void scalar_load4(const int32_t* row_, int o0, int o1, int o2, int o3, int (&e)[4]) {
+  // wave uniform by construction; made so explicitly, or the operands may arrive in vector registers
+  const int32_t* row = reinterpret_cast<const int32_t*>(uniform_ptr(reinterpret_cast<const char*>(row_)));
+  o0 = __builtin_amdgcn_readfirstlane(o0);
+  o1 = __builtin_amdgcn_readfirstlane(o1);
+  o2 = __builtin_amdgcn_readfirstlane(o2);
+  o3 = __builtin_amdgcn_readfirstlane(o3);
+  asm volatile(
+      "s_load_dword %0, %4, %5\n\t"
+      "s_load_dword %1, %4, %6\n\t"
+      "s_load_dword %2, %4, %7\n\t"
+      "s_load_dword %3, %4, %8\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(e[0]), "=&s"(e[1]), "=&s"(e[2]), "=&s"(e[3])
+      : "s"(row), "s"(o0 * 4), "s"(o1 * 4), "s"(o2 * 4), "s"(o3 * 4)
+      : "memory");
+}
+
+// Item number -> item with its key-block list (for a global-row workgroup: the wave's share of
+// the row).  All loads here are waited for before the function returns (scalar loads inside
+// their asm statement, the others by the compiler), so tile loads in flight are at most delayed.
+// Its first part: which row, which slice of the row's list (arithmetic only, no memory access).
+__device__ __forceinline__ void item_coords(const FwdParams& p, const WaveCtx& w, const Sched& sc, int t, Item& it,
+                                            int& list_lo, int& list_len, bool& row_global) {
+  const Pattern pat{p.nb, p.g, p.w, p.global_mode};
+  const Bf16Geom& geo = p.geo;
+  if (sc.global_wg) {
+    it.bh = (sc.wg / geo.g_wgs) * kXcd + sc.xcd;
+    const int gidx = sc.wg % geo.g_wgs;
+    const int row = gidx / geo.ng, u = gidx % geo.ng;
+    row_global = true;
+    it.j = pat.global_block(row);
+    it.chunk = u;
+    it.nchunks = geo.ng;
+    it.slot = it.bh * p.slots_per_bh + row * geo.ng + u;
+    list_lo = (u * kFwdWaves + w.wv) * geo.gw_len;
+    list_len = geo.gw_len;
+  } else {
+    it.bh = (t / geo.n_sitems) * kXcd + sc.xcd;
+    const int sitem = t % geo.n_sitems;
+    row_global = false;
+    it.j = pat.sparse_block(sitem / geo.cs);
+    it.chunk = sitem % geo.cs;
+    it.nchunks = geo.cs;
+    it.slot = it.bh * p.slots_per_bh + p.cmb_g_rows * p.cmb_g_n + sitem;
+    list_lo = it.chunk * kGlobalWaveLen;  // up to 16 key blocks per item (8 at the ITC base pattern)
+    list_len = kGlobalWaveLen;
+  }
+}
+
+__device__ __forceinline__ const char* query_tile(const FwdParams& p, int bh, int j) {
+  return static_cast<const char*>(p.Q) + (static_cast<size_t>(bh) * p.n + static_cast<size_t>(j) * kBlk) * (kDim * 2);
+}
+
+__device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, const Sched& sc, int t, Item& it) {
+  const Pattern pat{p.nb, p.g, p.w, p.global_mode};
+  const int lane = lane_again(w.lane);
+  int list_lo, list_len;
+  bool row_global;
+  item_coords(p, w, sc, t, it, list_lo, list_len, row_global);
+  const int bi = it.bh / p.H, h = it.bh % p.H;
+  const bool fast_list = !row_global && !p.kmask && p.rand_idx && p.r > 0 && p.g + p.w + p.r <= 64;
+  if (fast_list) {
+    const int32_t* rrow = p.rand_idx + (static_cast<size_t>(h) * p.nb + it.j) * p.r;
+    int rnd = -1;
+    for (int u0 = 0; u0 < p.r; u0 += 4) {
+      int e[4];
+      const int last = p.r - 1;
+      scalar_load4(rrow, u0, u0 + 1 < last ? u0 + 1 : last, u0 + 2 < last ? u0 + 2 : last,
+                   u0 + 3 < last ? u0 + 3 : last, e);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (lane == u0 + k && u0 + k < p.r) rnd = e[k];
+    }
+    it.cnt = finish_key_list_sparse(pat, p.r, it.j, rnd, list_lo, list_len, w.klist);
+  } else {
+    it.cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, row_global, list_lo,
+                                  list_len, w.klist);
+  }
+  // same wave wrote and reads the list: LDS keeps a wave's accesses in order, the compiler must too
+  asm volatile("" ::: "memory");
+  it.kl = w.klist[lane & (kGlobalWaveLen - 1)];
+  asm volatile("" ::: "memory");
+  it.any_partial = false;
+  if (p.kmask)
+    for (int i = 0; i < it.cnt; ++i)
+      it.any_partial |= key_valid_bits(p.kmask, bi, p.n, __builtin_amdgcn_readlane(it.kl, i)) != ~0ull;
+  // all of these are wave uniform; saying so keeps them (and what is computed from them) in
+  // scalar registers
+  it.bh = __builtin_amdgcn_readfirstlane(it.bh);
+  it.j = __builtin_amdgcn_readfirstlane(it.j);
+  it.chunk = __builtin_amdgcn_readfirstlane(it.chunk);
+  it.nchunks = __builtin_amdgcn_readfirstlane(it.nchunks);
+  it.slot = __builtin_amdgcn_readfirstlane(it.slot);
+  it.cnt = __builtin_amdgcn_readfirstlane(it.cnt);
+  it.any_partial = __builtin_amdgcn_readfirstlane(static_cast<int>(it.any_partial)) != 0;
+}
+
+// First tiles of an item that nobody has fetched ahead.  The query block takes the same road as a
+// key block: eight coalesced 1 KB loads into LDS (the V buffer, idle until the first block's V
+// arrives), then operand reads.  Register loads of the operand layout would touch every row of
+// the tile in each instruction and cost the address unit four times as many cache-line requests.
+// Leaves: K(0) in the K buffer, the scaled Q fragments in qb, V(0).t0 as the only load in flight.
+__device__ __forceinline__ void fresh_start(const FwdParams& p, const WaveCtx& w, const StraightOffsets& so,
+                                            const Item& item, bf16x8 (&qb)[2][4]) {
+  const ItemTiles ct(p, item);
+  tile_load_async_wave(ct.ktile(0), w.cx.lds_k_a, w.cx.voff);
+  tile_load_async_wave(ct.qtile, w.cx.lds_v_a, w.cx.voff);
+  wait_tile_loads<0>();
+  so.read(w.lds_v, qb);
+  wait_lds_reads();
+  half_load_async(ct.vtile(0), w.cx.lds_v_a, 0, w.cx.voff);
+}
+
+// The two tile streams of an item as global addresses, entry m in lane m (two registers each).
+// K stream: the item's K tiles; then, if an item follows, its query tile (twice: the second
+// request only rewrites what the first has brought).  V stream: the item's V tiles, then the next
+// item's first K tile.  So when an item's last pair is done, its successor's query tile sits in
+// the K buffer and its first K tile in the V buffer (the pairs' regular reads take them for K / V
+// fragments, which nothing uses).  Without a successor the streams end in the item's first tiles
+// again: requests whose data nobody uses, so that every pair issues the same loads and waits for
+// the same counts.
+struct TileStreams {
+  unsigned klo, khi, vlo, vhi;
+  __device__ __forceinline__ TileStreams(const FwdParams& p, const Item& it, const Item* next, int lane) {
+    const ItemTiles ct(p, it);
+    // What the lanes past the item's own tiles hold.  Computed here, with every lane active: these
+    // addresses read lane 0 of a list register, which must not happen inside a branch that lane 0
+    // does not take (the value of an inactive lane is not defined there).
+    unsigned long long k_tail, v_tail;
+    if (next) {
+      const ItemTiles nx(p, *next);
+      k_tail = reinterpret_cast<unsigned long long>(nx.qtile);
+      v_tail = reinterpret_cast<unsigned long long>(nx.ktile(0));
+    } else {
+      k_tail = reinterpret_cast<unsigned long long>(ct.ktile(0));
+      v_tail = reinterpret_cast<unsigned long long>(ct.vtile(0));
+    }
+    const unsigned long long off = static_cast<unsigned long long>(static_cast<unsigned>(it.kl)) << 13;
+    const bool own = lane < it.cnt;
+    const unsigned long long ka = own ? reinterpret_cast<unsigned long long>(ct.kbase) + off : k_tail;
+    const unsigned long long va = own ? reinterpret_cast<unsigned long long>(ct.vbase) + off : v_tail;
+    klo = static_cast<unsigned>(ka);
+    khi = static_cast<unsigned>(ka >> 32);
+    vlo = static_cast<unsigned>(va);
+    vhi = static_cast<unsigned>(va >> 32);
+  }
+  __device__ __forceinline__ const char* k(int m) const {
+    return reinterpret_cast<const char*>(
+        (static_cast<unsigned long long>(static_cast<unsigned>(__builtin_amdgcn_readlane(khi, m))) << 32) |
+        static_cast<unsigned>(__builtin_amdgcn_readlane(klo, m)));
+  }
+  __device__ __forceinline__ const char* v(int m) const {
+    return reinterpret_cast<const char*>(
+        (static_cast<unsigned long long>(static_cast<unsigned>(__builtin_amdgcn_readlane(vhi, m))) << 32) |
+        static_cast<unsigned>(__builtin_amdgcn_readlane(vlo, m)));
+  }
+};
+
+// The item's block pairs through the pipeline.
+// On entry, fresh: K(0) is in the K buffer, V(0).t0 is the only load outstanding.
+//           else : K(0)'s fragments are in `ka`, V(0).t0 and V(0).t1 are outstanding, in that order
+//                  (the previous item's last pairs fetched this one's first tiles, see below).
+// If `nx` is given, the item after this one rides at the end of the streams: its query tile as
+// one more tile of the K stream, its first K tile as one more of the V stream, so that both are
+// in LDS when this item's last pair is done (they are read as K / V fragments by the pairs'
+// regular reads, which nothing uses).
 __device__ __forceinline__ void fast_item(const PairCtx& cx, const StraightOffsets& so, const TransposedOffsets& to,
-                                          const bf16x8 (&qb)[2][4], int cnt, int kl, f32x16 (&o)[2][2],
-                                          float (&l_run)[2], long long* stamp = nullptr) {
-  auto tile_off = [&](int i) { return static_cast<size_t>(__builtin_amdgcn_readlane(kl, i)) * kTile; };
-  bf16x8 ka[2][4], va[2][2][2], p3[2];
+                                          const bf16x8 (&qb)[2][4], bf16x8 (&ka)[2][4], const FwdParams& p,
+                                          const Item& item, const Item* next, bool fresh,
+                                          f32x16 (&o)[2][2], float (&l_tot)[2]) {
+  bf16x8 va[2][2][2], p3[2];
   f32x16 sA;
-  float lr[2][2] = {{0.f, 0.f}, {0.f, 0.f}};  // [query tile][chain]
+  const RowSumOperand ones(lane_id());
+  f32x4 ls[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};  // per query tile
 #pragma unroll
   for (int a = 0; a < 2; ++a) {  // what the first pair "finishes": nothing
 #pragma unroll
@@ -354,38 +639,40 @@ __device__ __forceinline__ void fast_item(const PairCtx& cx, const StraightOffse
 #pragma unroll
       for (int e = 0; e < 8; ++e) va[1][a][b][e] = static_cast<__bf16>(0.f);
   }
-  // start of the stream: K(0) -> registers, then the loads a pair expects to find outstanding
-  read_k_half(so, cx.lds_k, 0, ka[0]);
-  read_k_half(so, cx.lds_k, 1, ka[1]);
-  wait_lds_reads();
-  if (cnt > 1) half_load_async(cx.kbase + tile_off(1), cx.lds_k_a, 0, cx.voff);
-  half_load_async(cx.vbase + tile_off(0), cx.lds_v_a, 1, cx.voff);
-  if (cnt > 1) wait_tile_loads<8>(); else wait_tile_loads<4>();
+  const int cnt = item.cnt;
+  const TileStreams ts(p, item, next, lane_id());
+
+  // start of the streams: K(0) -> registers, then the loads a pair expects to find outstanding
+  if (fresh) {
+    read_k_half(so, cx.lds_k, 0, ka[0]);
+    read_k_half(so, cx.lds_k, 1, ka[1]);
+    wait_lds_reads();
+    half_load_async(ts.k(1), cx.lds_k_a, 0, cx.voff);
+    half_load_async(ts.v(0), cx.lds_v_a, 1, cx.voff);
+  } else {
+    half_load_async(ts.k(1), cx.lds_k_a, 0, cx.voff);
+  }
+  wait_tile_loads<8>();
   read_v_half(to, cx.lds_v, 0, va[0]);
   unit_scores(ka[0], qb[0], sA);
-#ifdef BB_STAMPS
-  stamp[5] = __builtin_readcyclecounter();
-#endif
 
-  for (int i = 0; i < cnt; ++i) {
-    const bool more1 = i + 1 < cnt, more2 = i + 2 < cnt;
-    pair_step(cx, so, to, qb, ka, va, sA, p3, o, lr, more1, more2, more1 ? tile_off(i + 1) : 0,
-              more2 ? tile_off(i + 2) : 0);
-  }
-  // the last unit's share of O
-  unit_pv(va[1], p3, o[1]);
+  for (int i = 0; i < cnt; ++i)
+    pair_step(cx, so, to, qb, ka, va, sA, p3, o, ones, ls, ts.k(i + 1), ts.v(i + 1), ts.k(i + 2));
+  if (!next) wait_tile_loads<0>();  // requests past the end of the streams
+  // the last unit's share of O and of the row sums
+  unit_pv(va[1], p3, o[1], ones, ls[1]);
 #pragma unroll
-  for (int q = 0; q < 2; ++q) l_run[q] = lr[q][0] + lr[q][1];
+  for (int q = 0; q < 2; ++q) l_tot[q] = row_total(ls[q], lane_id() & 31);
 }
 
 // The classical recurrence (running maximum, rescale on every block), one block pair at a time
-// with synchronous tile loads: the fallback for items whose row sums left the safe range of the
-// reference-free path.  Scores are base-2 exponents already (the query fragments carry the
-// scale).  Leaves m_ref (exponent units), this lane's share of the row sums and O~.
+// with synchronous tile loads: the path of items with padded keys inside a block and the
+// fallback for items whose row sums left the safe range of the reference-free path.  Leaves m_ref (exponent
+// units), this lane's share of the row sums and O~.  Any load still in flight lands first.
 __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffsets& so, const TransposedOffsets& to,
-                                          const bf16x8 (&qb)[2][4], int cnt, int kl, int vlo, int vhi, bool masked,
+                                          const bf16x8 (&qb)[2][4], const FwdParams& p, const Item& item,
                                           f32x16 (&o)[2][2], float (&l_run)[2], float (&m_ref)[2]) {
-  const bf16x2 ones = {static_cast<__bf16>(1.f), static_cast<__bf16>(1.f)};
+  const ItemTiles it(p, item);
   zero_acc(o[0]);
   zero_acc(o[1]);
 #pragma unroll
@@ -393,16 +680,15 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
     m_ref[q] = neg_inf();
     l_run[q] = 0.f;
   }
-  for (int i = 0; i < cnt; ++i) {
-    const size_t off = static_cast<size_t>(__builtin_amdgcn_readlane(kl, i)) * kTile;
+  for (int i = 0; i < item.cnt; ++i) {
     uint64_t vbits = ~0ull;
-    if (masked)
-      vbits = (static_cast<uint64_t>(static_cast<unsigned>(__builtin_amdgcn_readlane(vhi, i))) << 32) |
-              static_cast<unsigned>(__builtin_amdgcn_readlane(vlo, i));
-    half_load_async(cx.kbase + off, cx.lds_k_a, 0, cx.voff);
-    half_load_async(cx.kbase + off, cx.lds_k_a, 1, cx.voff);
-    half_load_async(cx.vbase + off, cx.lds_v_a, 0, cx.voff);
-    half_load_async(cx.vbase + off, cx.lds_v_a, 1, cx.voff);
+    if (p.kmask) vbits = key_valid_bits(p.kmask, item.bh / p.H, p.n, __builtin_amdgcn_readlane(item.kl, i));
+    const char* kt = it.ktile(i);
+    const char* vt = it.vtile(i);
+    half_load_async(kt, cx.lds_k_a, 0, cx.voff);
+    half_load_async(kt, cx.lds_k_a, 1, cx.voff);
+    half_load_async(vt, cx.lds_v_a, 0, cx.voff);
+    half_load_async(vt, cx.lds_v_a, 1, cx.voff);
     wait_tile_loads<0>();
     bf16x8 ka[2][4], va[2][2][2];
     read_k_half(so, cx.lds_k, 0, ka[0]);
@@ -421,7 +707,7 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
         const unsigned mine = static_cast<unsigned>(vbits >> (32 * t + cx.hf * 4));
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          if (!((mine >> acc_row(r, 0)) & 1)) s[t][r] = neg_inf();
+          s[t][r] = ((mine >> acc_row(r, 0)) & 1) ? s[t][r] * cx.c : neg_inf();  // base-2 exponent
           mloc = fmaxf(mloc, s[t][r]);
         }
       }
@@ -443,11 +729,11 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
 #pragma unroll
           for (int kk = 0; kk < 8; kk += 2) {
             const int r = sgl * 8 + kk;
-            const bf16x2 pk = {static_cast<__bf16>(fast_exp2(s[t][r] - m_use)),
-                               static_cast<__bf16>(fast_exp2(s[t][r + 1] - m_use))};
+            const float p0 = fast_exp2(s[t][r] - m_use), p1 = fast_exp2(s[t][r + 1] - m_use);
+            const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
             pb[sgl][kk] = pk[0];
             pb[sgl][kk + 1] = pk[1];
-            l_run[q] = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run[q], false);
+            l_run[q] += p0 + p1;
           }
         unit_pv(va[t], pb, o[q]);
       }
@@ -455,254 +741,175 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
   }
 }
 
-// Query fragments times scale*log2(e), rounded to bf16 again.
-__device__ __forceinline__ void scale_fragments(bf16x8 (&f)[2][4], float c) {
+// Normalised bf16 output and LSE of a non-global item.  The accumulators hold O^T (a lane owns one
+// query and scattered groups of four d); they are turned through LDS (the K buffer) so that global
+// memory sees whole rows: 16 bytes per lane, consecutive lanes on consecutive addresses.
+__device__ __forceinline__ void store_rows_bf16(const FwdParams& p, const WaveCtx& w, const Item& it,
+                                                const f32x16 (&o)[2][2], const float (&inv)[2],
+                                                const float (&lse)[2]) {
+  const size_t row_blk = static_cast<size_t>(it.bh) * p.n + it.j * kBlk;  // first row of the query block
+  const int lane = lane_again(w.lane), hf = lane >> 5, col = lane & 31;
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
+  for (int q = 0; q < 2; ++q) {
+    if (hf == 0) p.LSE[row_blk + q * 32 + col] = lse[q];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+    for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) f[q][ks][e] = static_cast<__bf16>(static_cast<float>(f[q][ks][e]) * c);
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(o[q][dt][r4 * 4 + e] * inv[q]);
+        // d0 = 32 dt + 8 r4 + 4 hf: 16-byte chunk 4 dt + r4, upper or lower half of it
+        *reinterpret_cast<bf16x4*>(w.lds_k + tile_off_bf16(q * 32 + col, dt * 4 + r4) + hf * 8) = v;
+      }
+  }
+  wait_lds_reads();
+  __bf16* orow = static_cast<__bf16*>(p.O) + row_blk * kDim;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    u32x4 ov[4];
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+      ov[ii] = *reinterpret_cast<const u32x4*>(w.lds_k +
+                                               tile_off_bf16((half * 4 + ii) * 8 + (lane >> 3), lane & 7));
+    wait_lds_reads();  // after the second batch the K buffer may be refilled
+#pragma unroll
+    for (int ii = 0; ii < 4; ++ii)
+      *reinterpret_cast<u32x4*>(orow + ((half * 4 + ii) * 8 + (lane >> 3)) * kDim + (lane & 7) * 8) = ov[ii];
+  }
 }
 
-}  // namespace
-
-__global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
-void fwd_kernel_bf16(FwdParams p) {
-  __shared__ __attribute__((aligned(1024))) char lds_all[kFwdWaves][2 * kTile];  // per wave: K tile, V tile
-  __shared__ int klist_all[kFwdWaves][kGlobalWaveLen];
-  __shared__ float mrg_m[kFwdWaves][kBlk], mrg_l[kFwdWaves][kBlk];  // global rows: per-wave exponent, sum
-
-#ifdef BB_STAMPS
-  // development build: per-wave time stamps (shader clock) into the partial-result workspace
-  long long stamp[6] = {0, 0, 0, 0, 0, 0};
-  const long long rt0 = __builtin_amdgcn_s_memrealtime();
-  stamp[0] = __builtin_readcyclecounter();
-#define BB_STAMP(i) stamp[i] = __builtin_readcyclecounter()
-#else
-#define BB_STAMP(i)
-#endif
-  const Pattern pat{p.nb, p.g, p.w, p.global_mode};
-  const Bf16Geom& geo = p.geo;
-  const int lane = lane_id();
-  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, and the compiler should know
-  const int hf = lane >> 5, col = lane & 31;
-  char* const lds_kv = lds_all[wv];
-  char* const lds_k = lds_kv;
-  char* const lds_v = lds_kv + kTile;
-  int* const klist = klist_all[wv];
-
-  // Workgroup id -> work.  id % 8 is the die (XCD) the hardware dispatches to; each die gets
-  // whole (batch, head) slices so that a slice's K and V stay in its L2.  Within a die the
-  // global-row workgroups of all its slices come first: they are the longest (running them
-  // beside their own slice's other rows instead was measured 8 % slower).
-  WorkItem it;
-  int list_lo, list_len;
-  {
-    const int xcd = blockIdx.x % kXcd;
-    unsigned q = blockIdx.x / kXcd;
-    const unsigned n_gpart = static_cast<unsigned>(geo.bh_rounds) * geo.g_wgs;
-    if (q < n_gpart) {
-      it.bh = (q / geo.g_wgs) * kXcd + xcd;
-      const int gidx = q % geo.g_wgs;
-      const int row = gidx / geo.ng, u = gidx % geo.ng;
-      it.row_global = true;
-      it.j = pat.global_block(row);
-      it.chunk = u;
-      it.nchunks = geo.ng;
-      it.slot = it.bh * p.slots_per_bh + row * geo.ng + u;
-      list_lo = (u * kFwdWaves + wv) * geo.gw_len;
-      list_len = geo.gw_len;
-      if (it.bh >= p.BH) return;  // whole workgroup
-    } else {
-      q -= n_gpart;
-      it.bh = (q / geo.s_wgs) * kXcd + xcd;
-      const int sitem = (q % geo.s_wgs) * kFwdWaves + wv;
-      if (it.bh >= p.BH || sitem >= geo.n_sitems) return;  // no barrier follows for these workgroups
-      it.row_global = false;
-      it.j = pat.sparse_block(sitem / geo.cs);
-      it.chunk = sitem % geo.cs;
-      it.nchunks = geo.cs;
-      it.slot = it.bh * p.slots_per_bh + p.cmb_g_rows * p.cmb_g_n + sitem;
-      list_lo = it.chunk * kGlobalWaveLen;  // up to 16 key blocks per item (8 at the ITC base pattern)
-      list_len = kGlobalWaveLen;
-    }
-  }
-  const int bi = it.bh / p.H, h = it.bh % p.H;
-
-  const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;
-  const size_t qrow0 = bh_row0 + it.j * kBlk + col;  // tile A row of this lane; tile B is 32 rows on
-
-  PairCtx cx;
-  cx.kbase = uniform_ptr(static_cast<const char*>(p.K) + bh_row0 * (kDim * 2));
-  cx.vbase = uniform_ptr(static_cast<const char*>(p.V) + bh_row0 * (kDim * 2));
-  cx.lds_k = lds_k;
-  cx.lds_v = lds_v;
-  cx.hf = hf;
+// Partial triple (reference exponent, row sums, un-normalised O in fp32) of one slice of a row
+// that has several, for the merge kernel; O goes through the K buffer in two passes of 32 d.
+__device__ __forceinline__ void store_partial(const FwdParams& p, const WaveCtx& w, const Item& it,
+                                              const f32x16 (&o)[2][2], const float (&m_ref)[2],
+                                              const float (&l_tot)[2]) {
+  const int lane = lane_again(w.lane), hf = lane >> 5, col = lane & 31;
+  float* pml = p.part_ml + static_cast<size_t>(it.slot) * (2 * kBlk);
+  float* po = p.part_o + static_cast<size_t>(it.slot) * (kBlk * kDim);
 #pragma unroll
-  for (int par = 0; par < 2; ++par) {
-    const int row = par * 8 + (lane >> 3);
-    cx.voff[par] = (lane >> 3) * 128 + (((lane & 7) ^ tile_swizzle(row)) << 4);
-  }
-  cx.lds_k_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_k));
-  cx.lds_v_a = __builtin_amdgcn_readfirstlane(lds_addr(lds_v));
-
-  // The first key block is nearly always known before the list is: a global row's slice starts
-  // at its own offset unless padding removed blocks before it, every other row starts with the
-  // first global block.  Its tiles are asked for now, so that their flight overlaps the reads
-  // of the pattern table instead of following them.
-  // For a non-global row without a padding mask the row of the pattern table (one entry per
-  // lane) is asked for before anything else and waited for while the first tile is in flight,
-  // so the list is built under the flight of the tiles instead of after it.
-  const bool fast_list = !it.row_global && !p.kmask && p.rand_idx && p.r > 0 && p.g + p.w + p.r <= 64;
-  const int32_t* rentry = p.rand_idx + (static_cast<size_t>(h) * p.nb + it.j) * p.r + (lane < p.r ? lane : 0);
-  const char* qtile = static_cast<const char*>(p.Q) + (bh_row0 + it.j * kBlk) * (kDim * 2);
-
-  int spec = -1;
-  if (it.row_global) {
-    if (list_lo < p.nb) spec = list_lo;
-  } else if (it.chunk == 0 && p.g > 0) {
-    spec = pat.global_block(0);
-  }
-  // The query block takes the same road as a key block: eight coalesced 1 KB loads into LDS
-  // (the V buffer, idle until the first block's second half), then operand reads.  Register
-  // loads of the operand layout would touch every row of the tile in each instruction and cost
-  // the address unit four times as many cache-line requests.
-  int rnd = -1;
-  if (spec >= 0) {
-    const char* ktile = cx.kbase + static_cast<size_t>(spec) * kTile;
-    if (fast_list)
-      rnd = table_entry_then_tile(rentry, ktile, cx.lds_k_a, cx.voff);
-    else
-      tile_load_async_wave(ktile, cx.lds_k_a, cx.voff);
-    tile_load_async_wave(qtile, cx.lds_v_a, cx.voff);
-  } else if (fast_list) {
-    rnd = table_entry_then_tile(rentry, qtile, cx.lds_v_a, cx.voff);
-  } else {
-    tile_load_async_wave(qtile, cx.lds_v_a, cx.voff);
-  }
-
-  int cnt;
-  if (fast_list) {
-    if (lane >= p.r) rnd = -1;
-    cnt = finish_key_list_sparse(pat, p.r, it.j, rnd, list_lo, list_len, klist);
-  } else {
-    cnt = build_key_list_range(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global, list_lo,
-                               list_len, klist);
-  }
-  // same wave wrote and reads the list: LDS keeps a wave's accesses in order, the compiler must too
-  asm volatile("" ::: "memory");
-  const int kl = klist[lane & (kGlobalWaveLen - 1)];  // lane t holds list entry t % 16
-
-  // Validity bits of the listed key blocks: lane t holds those of list entry t (two registers).
-  // Read once per item, before the loop: a compiler-tracked load inside the loop would drain
-  // the tile loads in flight.
-  int vlo = -1, vhi = -1;
-  bool any_partial = false;
-  if (p.kmask) {
-    for (int i = 0; i < cnt; ++i) {
-      const uint64_t vb = key_valid_bits(p.kmask, bi, p.n, __builtin_amdgcn_readlane(kl, i));
-      if (lane == i) {
-        vlo = static_cast<int>(static_cast<unsigned>(vb));
-        vhi = static_cast<int>(static_cast<unsigned>(vb >> 32));
-      }
-      any_partial |= vb != ~0ull;
+  for (int q = 0; q < 2; ++q)
+    if (hf == 0) {
+      pml[q * 32 + col] = m_ref[q];
+      pml[kBlk + q * 32 + col] = l_tot[q];
     }
+#pragma unroll
+  for (int dt = 0; dt < 2; ++dt) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = o[q][dt][r4 * 4 + e];
+        *reinterpret_cast<f32x4*>(w.lds_k + tile_off_bf16(q * 32 + col, r4 * 2 + hf)) = v;
+      }
+    wait_lds_reads();
+#pragma unroll
+    for (int ii = 0; ii < 8; ++ii) {
+      const int row = ii * 8 + (lane >> 3), cc = lane & 7;
+      const f32x4 v = *reinterpret_cast<const f32x4*>(w.lds_k + tile_off_bf16(row, cc));
+      *reinterpret_cast<f32x4*>(po + row * kDim + dt * 32 + cc * 4) = v;
+    }
+    wait_lds_reads();
   }
+}
 
-  // Q^T operands (B of S^T = K Q^T) of the two query tiles: lane holds query `col` (+32 for
-  // tile B), d = 16*ks + 8*hf .. +8 -- the "straight" fragments of the Q tile.
+// The kernel's argument block as the cold functions below see it.  A reference to the kernel's own
+// copy would move that copy, and every later use of it in the hot loop, into scratch memory, and the
+// kernel-argument segment pointer is only defined inside the kernel itself.  So the kernel hands its
+// segment pointer down and the callee reads the structure again through scalar loads.
+typedef const FwdParams __attribute__((address_space(4))) * KernargPtr;
+
+__device__ __forceinline__ FwdParams params_from(const void* kernargs) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const char* u = uniform_ptr(static_cast<const char*>(kernargs));
+  return *(KernargPtr)(reinterpret_cast<uintptr_t>(u));
+#else
+  return FwdParams{};
+#endif
+}
+
+__device__ __forceinline__ const void* kernel_kernargs() {
+#if defined(__HIP_DEVICE_COMPILE__)
+  return (const void*)(__builtin_amdgcn_kernarg_segment_ptr());
+#else
+  return nullptr;
+#endif
+}
+
+// One non-global item by the classical recurrence, from its first load to its last store: the path
+// of items with padded keys inside a block or without any key block, and of items whose row sums
+// left the safe range of the pipelined path.  A function of its own, so that its registers are
+// not the persistent loop's problem.
+__device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t) {
+  const FwdParams p = params_from(kernargs);
+  const WaveCtx w(p.c);
+  const Sched sc(p);
+  const StraightOffsets so(w.lane);
+  const TransposedOffsets to(w.lane);
+  Item it;
+  make_item(p, w, sc, t, it);
+  wait_tile_loads<0>();
   bf16x8 qb[2][4];
-  const StraightOffsets so(lane);
-  const TransposedOffsets to(lane);
-  const bool guessed = cnt > 0 && __builtin_amdgcn_readlane(kl, 0) == spec;
-  wait_tile_loads<0>();  // Q was issued after the guessed K tile: when it has landed, so has K
-  if (!guessed && cnt > 0)  // wrong guess (or none): the right K tile is asked for now
-    tile_load_async_wave(cx.kbase + static_cast<size_t>(__builtin_amdgcn_readlane(kl, 0)) * kTile, cx.lds_k_a, cx.voff);
-  so.read(lds_v, qb);
-  wait_lds_reads();
-  if (cnt > 0)
-    half_load_async(cx.vbase + static_cast<size_t>(__builtin_amdgcn_readlane(kl, 0)) * kTile, cx.lds_v_a, 0, cx.voff);
-  scale_fragments(qb, p.c);
+  f32x16 o[2][2];
+  float l_run[2], m_ref[2], l_tot[2];
+  if (it.cnt > 0) {
+    tile_load_async_wave(ItemTiles(p, it).qtile, w.cx.lds_v_a, w.cx.voff);
+    wait_tile_loads<0>();
+    so.read(w.lds_v, qb);
+    wait_lds_reads();
+    }
+  slow_item(w.cx, so, to, qb, p, it, o, l_run, m_ref);
+#pragma unroll
+  for (int q = 0; q < 2; ++q) l_tot[q] = half_sum(l_run[q]);
+  if (it.nchunks == 1) {
+    float inv[2], lse[2];
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      inv[q] = l_tot[q] > 0.f ? 1.f / l_tot[q] : 0.f;
+      lse[q] = l_tot[q] > 0.f ? (m_ref[q] + fast_log2(l_tot[q])) * kLn2 : neg_inf();
+    }
+    store_rows_bf16(p, w, it, o, inv, lse);
+  } else {
+    store_partial(p, w, it, o, m_ref, l_tot);
+  }
+}
 
-  BB_STAMP(1);
-  f32x16 o[2][2];  // [query tile][d tile]: O^T accumulators
+// One global query block by a whole workgroup: 16 key blocks per wave, the four waves' (m, l, O~)
+// merged in LDS.  A function of its own for the same reason.
+__device__ __attribute__((noinline)) void global_row_workgroup(const void* kernargs) {
+  const FwdParams p = params_from(kernargs);
+  const WaveCtx w(p.c);
+  const Sched sc(p);
+  const StraightOffsets so(w.lane);
+  const TransposedOffsets to(w.lane);
+  const int lane = w.lane, wv = w.wv, hf = w.hf, col = w.col;
+  Item cur;
+  make_item(p, w, sc, 0, cur);
+  bf16x8 qb[2][4], ka[2][4];
+  f32x16 o[2][2];
+  float m_ref[2] = {0.f, 0.f};  // reference exponents (base-2 units); halves agree
+  float l_tot[2] = {0.f, 0.f};  // row sums of 2^(s - m_ref)
   zero_acc(o[0]);
   zero_acc(o[1]);
-  float m_ref[2] = {0.f, 0.f};  // reference exponents (base-2 units); halves agree
-  float l_run[2] = {0.f, 0.f};  // this lane's share of sum 2^(s - m_ref)
-  float l_tot[2] = {0.f, 0.f};
-  if (cnt > 0) {
-    if (!guessed) wait_tile_loads<4>();  // the K tile asked for late; V(0).t0 may still fly
-    bool bad = any_partial;  // per-key masking is only in the slow path
-    if (!any_partial) {
-      BB_STAMP(2);
-#ifdef BB_STAMPS
-      fast_item(cx, so, to, qb, cnt, kl, o, l_run, stamp);
-#else
-      fast_item(cx, so, to, qb, cnt, kl, o, l_run);
-#endif
-      BB_STAMP(3);
+  if (cur.cnt > 0) {
+    fresh_start(p, w, so, cur, qb);
+    float l_run[2] = {0.f, 0.f};
+    bool bad = cur.any_partial;  // per-key masking is only in the slow path
+    if (!cur.any_partial) {
+      fast_item(w.cx, so, to, qb, ka, p, cur, nullptr, true, o, l_tot);
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        l_tot[q] = half_sum(l_run[q]);
-        bad |= !(l_tot[q] >= kSumLo && l_tot[q] <= kSumHi);
-      }
+      for (int q = 0; q < 2; ++q) bad |= !(l_tot[q] >= kSumLo && l_tot[q] <= kSumHi);
     }
     if (__any(bad)) {
-      slow_item(cx, so, to, qb, cnt, kl, vlo, vhi, p.kmask != nullptr, o, l_run, m_ref);
+      slow_item(w.cx, so, to, qb, p, cur, o, l_run, m_ref);
 #pragma unroll
       for (int q = 0; q < 2; ++q) l_tot[q] = half_sum(l_run[q]);
     }
   } else {
     m_ref[0] = m_ref[1] = neg_inf();
   }
-
-  // ---- finalise.  The accumulators hold O^T (a lane owns one query and scattered groups
-  // of four d); they are turned through LDS (free now) so that global memory sees whole
-  // rows: 16 bytes per lane, consecutive lanes on consecutive addresses.
-  const size_t row_blk = bh_row0 + it.j * kBlk;  // first row of the query block
-  if (!it.row_global && it.nchunks == 1) {
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const float inv = l_tot[q] > 0.f ? 1.f / l_tot[q] : 0.f;
-      if (hf == 0)
-        p.LSE[qrow0 + q * 32] = l_tot[q] > 0.f ? (m_ref[q] + fast_log2(l_tot[q])) * kLn2 : neg_inf();
-#pragma unroll
-      for (int dt = 0; dt < 2; ++dt)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          bf16x4 v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = static_cast<__bf16>(o[q][dt][r4 * 4 + e] * inv);
-          // d0 = 32 dt + 8 r4 + 4 hf: 16-byte chunk 4 dt + r4, upper or lower half of it
-          *reinterpret_cast<bf16x4*>(lds_kv + tile_off_bf16(q * 32 + col, dt * 4 + r4) + hf * 8) = v;
-        }
-    }
-    wait_lds_reads();
-    __bf16* orow = static_cast<__bf16*>(p.O) + row_blk * kDim;
-#pragma unroll
-    for (int ii = 0; ii < 8; ++ii) {
-      const int row = ii * 8 + (lane >> 3), chunk = lane & 7;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(lds_kv + tile_off_bf16(row, chunk));
-      *reinterpret_cast<u32x4*>(orow + row * kDim + chunk * 8) = v;
-    }
-#ifdef BB_STAMPS
-    __builtin_amdgcn_s_waitcnt(0);
-    stamp[4] = __builtin_readcyclecounter();
-    if (lane == 0) {
-      long long* dst = reinterpret_cast<long long*>(p.part_o) + (static_cast<size_t>(blockIdx.x) * kFwdWaves + wv) * 16;
-      for (int i = 0; i < 5; ++i) dst[i] = stamp[i];
-      dst[5] = cnt;
-      dst[7] = stamp[5];
-      dst[8] = rt0;
-      dst[9] = __builtin_amdgcn_s_memrealtime();
-      dst[6] = __builtin_amdgcn_s_getreg((31 << 11) | 4) /* HW_ID */;
-    }
-#endif
-    return;
-  }
-
   // Un-normalised O of this wave as an fp32 [64 q][64 d] tile in its LDS region: d 0..31 in the
   // first 8 KB, d 32..63 in the second, each laid out like a bf16 tile (128-byte rows of 32 floats).
 #pragma unroll
@@ -714,31 +921,8 @@ void fwd_kernel_bf16(FwdParams p) {
         f32x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = o[q][dt][r4 * 4 + e];
-        *reinterpret_cast<f32x4*>(lds_kv + dt * kTile + tile_off_bf16(q * 32 + col, r4 * 2 + hf)) = v;
+        *reinterpret_cast<f32x4*>(w.lds_kv + dt * kTile + tile_off_bf16(q * 32 + col, r4 * 2 + hf)) = v;
       }
-
-  if (!it.row_global) {
-    // slice of a non-global row with several slices: partial triple for the merge kernel
-    float* pml = p.part_ml + static_cast<size_t>(it.slot) * (2 * kBlk);
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-      if (hf == 0) {
-        pml[q * 32 + col] = m_ref[q];
-        pml[kBlk + q * 32 + col] = l_tot[q];
-      }
-    wait_lds_reads();
-    float* po = p.part_o + static_cast<size_t>(it.slot) * (kBlk * kDim);
-#pragma unroll
-    for (int ii = 0; ii < 16; ++ii) {
-      const int row = ii * 4 + (lane >> 4), cc = lane & 15;
-      const f32x4 v = *reinterpret_cast<const f32x4*>(lds_kv + (cc >> 3) * kTile + tile_off_bf16(row, cc & 7));
-      *reinterpret_cast<f32x4*>(po + row * kDim + cc * 4) = v;
-    }
-    return;
-  }
-
-  // ---- global row: merge the four waves' (m, l, O~) in LDS.  Wave w then owns query rows
-  // 16w .. 16w+15; a lane owns 16 d columns of one row.
 #pragma unroll
   for (int q = 0; q < 2; ++q)
     if (hf == 0) {
@@ -746,69 +930,298 @@ void fwd_kernel_bf16(FwdParams p) {
       mrg_l[wv][q * 32 + col] = l_tot[q];
     }
   __syncthreads();  // all four waves of a global workgroup arrive here
-  {
-    const int q = wv * 16 + (lane >> 2), part = lane & 3;
-    float M = neg_inf();
+  // wave w now owns query rows 16w .. 16w+15; a lane owns 16 d columns of one row
+  const size_t row_blk = static_cast<size_t>(cur.bh) * p.n + cur.j * kBlk;
+  const int q = wv * 16 + (lane >> 2), part = lane & 3;
+  float M = neg_inf();
 #pragma unroll
-    for (int v = 0; v < kFwdWaves; ++v) M = fmaxf(M, mrg_m[v][q]);
-    f32x4 acc[4];
+  for (int v = 0; v < kFwdWaves; ++v) M = fmaxf(M, mrg_m[v][q]);
+  f32x4 acc[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float L = 0.f;
-    if (M != neg_inf()) {
+  for (int e = 0; e < 4; ++e) acc[e] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float L = 0.f;
+  if (M != neg_inf()) {
 #pragma unroll
-      for (int v = 0; v < kFwdWaves; ++v) {
-        const float mv = mrg_m[v][q];
-        const float wgt = (mv == neg_inf()) ? 0.f : fast_exp2(mv - M);
-        L += mrg_l[v][q] * wgt;
+    for (int v = 0; v < kFwdWaves; ++v) {
+      const float mv = mrg_m[v][q];
+      const float wgt = (mv == neg_inf()) ? 0.f : fast_exp2(mv - M);
+      L += mrg_l[v][q] * wgt;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int cc = part * 4 + e;
-          const f32x4 x =
-              *reinterpret_cast<const f32x4*>(lds_all[v] + (cc >> 3) * kTile + tile_off_bf16(q, cc & 7));
+      for (int e = 0; e < 4; ++e) {
+        const int cc = part * 4 + e;
+        const f32x4 x = *reinterpret_cast<const f32x4*>(lds_all[v] + (cc >> 3) * kTile + tile_off_bf16(q, cc & 7));
 #pragma unroll
-          for (int z = 0; z < 4; ++z) acc[e][z] += x[z] * wgt;
-        }
+        for (int z = 0; z < 4; ++z) acc[e][z] += x[z] * wgt;
       }
     }
-    const size_t row = row_blk + q;
-    if (it.nchunks == 1) {
-      const float inv = L > 0.f ? 1.f / L : 0.f;
-      if (part == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
-      bf16x8 v0, v1;
+  }
+  const size_t row = row_blk + q;
+  if (cur.nchunks == 1) {
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    if (part == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
+    bf16x8 v0, v1;
 #pragma unroll
-      for (int z = 0; z < 4; ++z) {
-        v0[z] = static_cast<__bf16>(acc[0][z] * inv);
-        v0[4 + z] = static_cast<__bf16>(acc[1][z] * inv);
-        v1[z] = static_cast<__bf16>(acc[2][z] * inv);
-        v1[4 + z] = static_cast<__bf16>(acc[3][z] * inv);
-      }
-      bf16x8* dst = reinterpret_cast<bf16x8*>(static_cast<__bf16*>(p.O) + row * kDim + part * 16);
-      dst[0] = v0;
-      dst[1] = v1;
-    } else {
-      // one of several workgroups of a long global row: merged partial triple for the merge kernel
-      float* pml = p.part_ml + static_cast<size_t>(it.slot) * (2 * kBlk);
-      if (part == 0) {
-        pml[q] = L > 0.f ? M : neg_inf();
-        pml[kBlk + q] = L;
-      }
-      f32x4* dst =
-          reinterpret_cast<f32x4*>(p.part_o + static_cast<size_t>(it.slot) * (kBlk * kDim) + q * kDim + part * 16);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) dst[e] = acc[e];
+    for (int z = 0; z < 4; ++z) {
+      v0[z] = static_cast<__bf16>(acc[0][z] * inv);
+      v0[4 + z] = static_cast<__bf16>(acc[1][z] * inv);
+      v1[z] = static_cast<__bf16>(acc[2][z] * inv);
+      v1[4 + z] = static_cast<__bf16>(acc[3][z] * inv);
     }
+    bf16x8* dst = reinterpret_cast<bf16x8*>(static_cast<__bf16*>(p.O) + row * kDim + part * 16);
+    dst[0] = v0;
+    dst[1] = v1;
+  } else {
+    // one of several workgroups of a long global row: merged partial triple for the merge kernel
+    float* pml = p.part_ml + static_cast<size_t>(cur.slot) * (2 * kBlk);
+    if (part == 0) {
+      pml[q] = L > 0.f ? M : neg_inf();
+      pml[kBlk + q] = L;
+    }
+    f32x4* dst =
+        reinterpret_cast<f32x4*>(p.part_o + static_cast<size_t>(cur.slot) * (kBlk * kDim) + q * kDim + part * 16);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) dst[e] = acc[e];
   }
 }
 
-int launch_fwd_bf16_main(const FwdParams& p, hipStream_t stream) {
-  const unsigned grid = static_cast<unsigned>(kXcd) * p.geo.bh_rounds * (p.geo.g_wgs + p.geo.s_wgs);
-  if (grid == 0) return BB_OK;
-#ifdef BB_EXP_ONEWAVE
-  hipLaunchKernelGGL(fwd_kernel_bf16, dim3(grid), dim3(kFwdThreads), 28 * 1024, stream, p);  // one workgroup per CU
+}  // namespace
+
+__global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
+void fwd_kernel_bf16(FwdParams p) {
+  const Sched sc(p);
+  if (sc.global_wg) {
+    if ((sc.wg / p.geo.g_wgs) * kXcd + sc.xcd < static_cast<unsigned>(p.BH)) global_row_workgroup(kernel_kernargs());
+    return;
+  }
+  const WaveCtx w(p.c);
+  const PairCtx& cx = w.cx;
+  const int lane = w.lane;
+  char* const lds_k = w.lds_k;
+  char* const lds_v = w.lds_v;
+  const StraightOffsets so(lane);
+  const TransposedOffsets to(lane);
+  const int n_items_die = sc.n_items_die, wave_stride = sc.wave_stride;
+  const int t_item = static_cast<int>(sc.wg - sc.n_gpart) * kFwdWaves + w.wv;  // first item of this wave
+  if (t_item >= n_items_die) return;
+
+  bf16x8 qb[2][4];  // Q^T operands (B of S^T = K Q^T): lane holds query `col` (+32 for tile B),
+                    // d = 16*ks + 8*hf .. +8 -- the "straight" fragments of the Q tile, scaled
+  bf16x8 ka[2][4];  // K fragments of the pair in work (they cross the item boundary)
+  f32x16 o[2][2];   // [query tile][d tile]: O^T accumulators
+
+#ifdef BB_STAMPS
+  // development build (-DBB_STAMPS): per-wave time accounting into the partial-result workspace,
+  // 16 x 8 bytes per wave: start and end on the constant 100 MHz clock, items done, shader-clock
+  // sums per phase of the persistent loop
+  const long long rt0 = __builtin_amdgcn_s_memrealtime();
+  long long acc_t[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  long long st_t[4] = {0, 0, 0, 0};  // first start in detail: lists, first tiles, operands ready
+  long long tprev = __builtin_readcyclecounter();
+  int n_done = 0;
+#define BB_STAMP(i) do { const long long tn__ = __builtin_readcyclecounter(); acc_t[i] += tn__ - tprev; tprev = tn__; } while (0)
 #else
-  hipLaunchKernelGGL(fwd_kernel_bf16, dim3(grid), dim3(kFwdThreads), 0, stream, p);
+#define BB_STAMP(i)
 #endif
+  // ---- persistent wave: the die's non-global items t_item, t_item + wave_stride, ...
+  // Items that cannot take the pipelined path (padded keys inside a block, no key block at all,
+  // or -- found out afterwards -- row sums outside the safe range) are put on a list and done
+  // by the classical recurrence when the stream has ended; the host sizes the grid so that a
+  // wave has at most 64 items (a lane of `redo` each).
+  int redo = 0;       // the list: lane t holds the number of the t-th such item
+  int n_redo = 0;
+  auto push_redo = [&](int t) {
+    if (lane == n_redo) redo = t;
+    n_redo = __builtin_amdgcn_readfirstlane(n_redo + 1);
+  };
+  // the next item at or after t that takes the pipelined path (others go to the list)
+  auto next_fast = [&](int t, Item& it) {
+    int found = -1;
+    for (; t < n_items_die; t += wave_stride) {
+      make_item(p, w, sc, t, it);
+      if (it.cnt > 0 && !it.any_partial) {
+        found = t;
+        break;
+      }
+      push_redo(t);
+    }
+    return __builtin_amdgcn_readfirstlane(found);
+  };
+
+  // cur: the item in work; nxt: the one after it (its list is needed before cur's last pairs,
+  // which fetch its first tiles); nn: the one after that, built while few loads are in flight.
+  // Where the first item's row is does not depend on the pattern table: its query tile is
+  // requested (into the K buffer) before anything else, and the table is read under that flight.
+  Item cur, nxt, nn;
+  {
+    int lo_, len_;
+    bool rg_;
+    item_coords(p, w, sc, t_item, cur, lo_, len_, rg_);
+    tile_load_async_wave(query_tile(p, __builtin_amdgcn_readfirstlane(cur.bh), __builtin_amdgcn_readfirstlane(cur.j)),
+                         cx.lds_k_a, cx.voff);
+  }
+  int t_cur = next_fast(t_item, cur);
+  int t_nxt = -1;
+#ifdef BB_STAMPS
+  st_t[0] = __builtin_readcyclecounter() - tprev;
+#endif
+  if (t_cur < 0) wait_tile_loads<0>();  // nothing for the pipelined path: let the request land
+  if (t_cur >= 0) {
+    bf16x8 va[2][2][2], p3[2];
+    f32x16 sA;
+    const RowSumOperand ones(lane_again(lane));
+    f32x4 ls[2];
+    // what the first pair of an item "finishes": nothing
+    auto reset_item_state = [&]() {
+      zero_acc(o[0]);
+      zero_acc(o[1]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        ls[a] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) p3[a][e] = static_cast<__bf16>(0.f);
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) va[1][a][b][e] = static_cast<__bf16>(0.f);
+      }
+    };
+    // pairs this wave still has to do, roughly (for its issue priority)
+    const int pairs_per_item = p.geo.cs > 1 ? kGlobalWaveLen : (p.g + p.w + p.r < kGlobalWaveLen ? p.g + p.w + p.r : kGlobalWaveLen);
+    int rem_pairs = __builtin_amdgcn_readfirstlane(((n_items_die - t_cur + wave_stride - 1) / wave_stride) * pairs_per_item);
+
+    // start of the first item.  Skipped items ahead of it: the request above was for another row.
+    wait_tile_loads<0>();
+    if (t_cur != t_item) {
+      tile_load_async_wave(query_tile(p, cur.bh, cur.j), cx.lds_k_a, cx.voff);
+      wait_tile_loads<0>();
+    }
+    so.read(lds_k, qb);
+    wait_lds_reads();
+    {
+      // K(0) and V(0) together; the next item's list is made while they fly
+      const ItemTiles ct(p, cur);
+      tile_load_async_wave(ct.ktile(0), cx.lds_k_a, cx.voff);
+      const char* v0 = uniform_ptr(ct.vtile(0));
+      half_load_async(v0, cx.lds_v_a, 0, cx.voff);
+      half_load_async(v0, cx.lds_v_a, 1, cx.voff);
+    }
+#ifdef BB_STAMPS
+    st_t[2] = __builtin_readcyclecounter() - tprev;
+#endif
+    t_nxt = next_fast(t_cur + wave_stride, nxt);  // (scalar loads only, unless there is a padding mask)
+    TileStreams ts(p, cur, t_nxt >= 0 ? &nxt : nullptr, lane_again(lane));
+    int cnt = __builtin_amdgcn_readfirstlane(cur.cnt);  // pairs of the item in work
+      reset_item_state();
+#ifdef BB_STAMPS
+    st_t[1] = __builtin_readcyclecounter() - tprev;
+#endif
+    wait_tile_loads<8>();  // K(0)
+    read_k_half(so, lds_k, 0, ka[0]);
+    read_k_half(so, lds_k, 1, ka[1]);
+    wait_lds_reads();
+    half_load_async(ts.k(1), cx.lds_k_a, 0, cx.voff);
+    wait_tile_loads<8>();  // V(0).t0
+    read_v_half(to, lds_v, 0, va[0]);
+    unit_scores(ka[0], qb[0], sA);
+    BB_STAMP(0);
+
+    for (int i = 0;;) {
+      if ((rem_pairs & 3) == 3 || i == 0) set_issue_priority(rem_pairs);
+      pair_step(cx, so, to, qb, ka, va, sA, p3, o, ones, ls, ts.k(i + 1), ts.v(i + 1), ts.k(i + 2));
+      rem_pairs = __builtin_amdgcn_readfirstlane(rem_pairs - 1);
+      i = __builtin_amdgcn_readfirstlane(i + 1);
+      if (__builtin_expect(i < cnt, 1)) continue;  // (the register allocator should favour the pairs)
+
+      // ---- item boundary.  The last unit's share of O, the row sums, the range check.
+      BB_STAMP(1);
+      unit_pv(va[1], p3, o[1], ones, ls[1]);
+      bool bad = false;
+      float inv[2], lse[2], lsum[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const float l = row_total(ls[q], w.col);
+        bad |= !(l >= kSumLo && l <= kSumHi);
+        lsum[q] = l;
+        inv[q] = 1.f / l;
+        lse[q] = fast_log2(l) * kLn2;
+      }
+      const bool redo_cur = __any(bad);
+      if (redo_cur) push_redo(t_cur);
+
+      // the list of the item after the next: here at most four tile loads are in flight, so the
+      // waits that building it may need (compiler-placed, for all loads) cost little
+      int t_nn = -1;
+      BB_STAMP(2);
+      if (t_nxt >= 0) {
+        t_nn = next_fast(t_nxt + wave_stride, nn);
+        BB_STAMP(3);
+        // The next item's query tile is in the K buffer, its first K tile in the V buffer (the
+        // second half may still be landing).  Both go to registers, its first V tile is requested,
+        // and this item's output is written under that flight.
+        wait_tile_loads<0>();
+        so.read(lds_k, qb);
+        read_k_half(so, lds_v, 0, ka[0]);
+        read_k_half(so, lds_v, 1, ka[1]);
+        wait_lds_reads();
+        const char* v0 = uniform_ptr(ItemTiles(p, nxt).vtile(0));
+        half_load_async(v0, cx.lds_v_a, 0, cx.voff);
+        half_load_async(v0, cx.lds_v_a, 1, cx.voff);
+      }
+
+      BB_STAMP(4);
+      if (t_nxt < 0) wait_tile_loads<0>();  // requests past the end of the streams
+      // ---- output, through the K buffer (free now)
+      if (!redo_cur) {
+        if (cur.nchunks == 1) {
+          store_rows_bf16(p, w, cur, o, inv, lse);
+        } else {
+          const float zero[2] = {0.f, 0.f};
+          store_partial(p, w, cur, o, zero, lsum);
+        }
+      }
+      BB_STAMP(5);
+#ifdef BB_STAMPS
+      ++n_done;
+#endif
+      if (t_nxt < 0) break;
+
+      // ---- the next item's stream starts (its K(0) fragments are in registers, V(0) is in flight)
+          cur = nxt;
+      t_cur = t_nxt;
+      nxt = nn;
+      t_nxt = t_nn;
+      ts = TileStreams(p, cur, t_nxt >= 0 ? &nxt : nullptr, lane_again(lane));
+      reset_item_state();
+      cnt = __builtin_amdgcn_readfirstlane(cur.cnt);
+      half_load_async(ts.k(1), cx.lds_k_a, 0, cx.voff);
+      wait_tile_loads<8>();
+      read_v_half(to, lds_v, 0, va[0]);
+      unit_scores(ka[0], qb[0], sA);
+      i = 0;
+      BB_STAMP(6);
+    }
+  }
+#ifdef BB_STAMPS
+  if (lane == 0) {
+    long long* dst = reinterpret_cast<long long*>(p.part_o) + (static_cast<size_t>(blockIdx.x) * kFwdWaves + w.wv) * 16;
+    dst[0] = rt0;
+    dst[1] = __builtin_amdgcn_s_memrealtime();
+    dst[2] = n_done;
+    for (int i = 0; i < 7; ++i) dst[3 + i] = acc_t[i];
+    dst[10] = st_t[0];
+    dst[11] = st_t[1];
+    dst[12] = st_t[2];
+  }
+#endif
+
+  // ---- the listed items, by the classical recurrence
+  for (int u = 0; u < n_redo; ++u) redo_item(kernel_kernargs(), __builtin_amdgcn_readlane(redo, u));
+}
+
+int launch_fwd_bf16_main(const FwdParams& p, hipStream_t stream) {
+  const unsigned grid = static_cast<unsigned>(kXcd) * (p.geo.bh_rounds * p.geo.g_wgs + p.geo.p_wgs);
+  if (grid == 0) return BB_OK;
+  hipLaunchKernelGGL(fwd_kernel_bf16, dim3(grid), dim3(kFwdThreads), 0, stream, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     fprintf(stderr, "bigbird: launch of fwd_kernel_bf16 failed: %s\n", hipGetErrorString(e));

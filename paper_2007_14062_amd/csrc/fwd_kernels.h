@@ -7,9 +7,9 @@
 namespace bb {
 
 // Work decomposition of the bf16 forward.  Workgroups have four independent waves.
-//   sparse workgroup: four consecutive items (non-global query block x slice of up to 16 key
-//   blocks: 8 at the ITC base pattern);
-//   global workgroup: one global query block x up to 64 key blocks, 16 per wave, merged in LDS.
+//   global workgroup: one global query block x up to 64 key blocks, 16 per wave, merged in LDS;
+//   persistent workgroup: its waves take the die's other items (non-global query block x slice
+//   of up to 16 key blocks: 8 at the ITC base pattern) in turn, wave w the items w, w + W, ...
 // A global row longer than 64 key blocks takes several workgroups whose merged partial
 // results go through the merge kernel, as do sparse rows with more than one slice.
 constexpr int kGlobalWaveLen = 16;  // most key blocks a wave of a global workgroup takes
@@ -19,7 +19,8 @@ struct Bf16Geom {
   int ng;        // workgroups per global row: ceil(nb / (4 * gw_len))
   int cs;        // slices per non-global row: ceil(min(g + w + r, nb) / 16)
   int n_sitems;  // (nb - g) * cs
-  int s_wgs;     // sparse workgroups per (batch, head): ceil(n_sitems / 4)
+  int s_wgs;     // ceil(n_sitems / 4): workgroups the non-global items of one (batch, head) would fill
+  int p_wgs;     // persistent workgroups per die: their waves share out the die's non-global items
   int g_wgs;     // global workgroups per (batch, head): g * ng
   int bh_rounds; // ceil(B*H / 8)
 };

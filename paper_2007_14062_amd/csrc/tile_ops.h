@@ -27,7 +27,8 @@ __device__ __forceinline__ void tile_load_async(const char* gtile, unsigned lds,
   for (int hh = 0; hh < 2; ++hh)
     asm volatile(
         "s_mov_b32 m0, %2\n\t"
-        "s_nop 0\n\t"  // a scalar write of M0 needs one wait state before an LDS-DMA load reads it
+        "s_nop 4\n\t"  // wait states the compiler cannot see to from outside: M0 written by a scalar instruction (1) and an
+                       // address register pair that a vector instruction (v_readlane) may just have written (5)
         "global_load_lds_dwordx4 %0, %1\n\t"
         "global_load_lds_dwordx4 %0, %1 offset:2048"
         :
@@ -45,7 +46,7 @@ __device__ __forceinline__ unsigned lds_addr(const void* p) {
 __device__ __forceinline__ void vec_load_async(const float* gvec, unsigned lds, unsigned lane) {
   asm volatile(
       "s_mov_b32 m0, %2\n\t"
-      "s_nop 0\n\t"
+      "s_nop 4\n\t"
       "global_load_lds_dword %0, %1"
       :
       : "v"(lane * 4u), "s"(gvec), "s"(lds)
