@@ -129,6 +129,27 @@ int bigbird_attn_fwd(const void* Q, const void* K, const void* V, void* O, float
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * bigbird_attn_fwd for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, checks, kernels and results as
+ * bigbird_attn_fwd, without the workspace: the scratch memory is a static device
+ * array of BIGBIRD_STATIC_SCRATCH_BYTES inside the library (one per GPU, held
+ * until the process ends).  The call allocates and frees nothing.  Sizes for which
+ * bigbird_attn_workspace_bytes(..., need_bwd = 0) exceeds that limit are refused
+ * with BB_ERR_WORKSPACE and a message on stderr.  The device the arrays live on is
+ * the current device of the calling thread (hip_stream must belong to it);
+ * BB_ERR_LAUNCH if the array's address cannot be obtained.  All calls on one GPU
+ * share its array, which keeps the previous call's partial results: nothing in it
+ * has to be cleared between calls, but calls that overlap in time on one GPU
+ * (different streams, different threads) race and give undefined results.
+ */
+#define BIGBIRD_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int bigbird_attn_fwd_static(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                            const int32_t* rand_idx, const uint8_t* key_padding_mask,
+                            int B, int H, int n, int d, int b, int g, int w, int r,
+                            float scale, int dtype, int global_mode, void* hip_stream);
+
+/*
  * Backward pass (the paper gives none: calculus on eq. (AT)).  With P the row
  * softmax recomputed from Q, K and LSE:
  *   dV = P^T dO;  dP = dO V^T;  D_i = sum_c dO_ic O_ic;  dS = P o (dP - D);

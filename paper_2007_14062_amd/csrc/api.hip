@@ -4,6 +4,8 @@
 #include "fwd_kernels.h"
 
 #include <cmath>
+#include <cstdio>
+#include <mutex>
 
 namespace {
 
@@ -84,11 +86,13 @@ extern "C" size_t bigbird_attn_workspace_bytes(int B, int H, int n, int d, int b
   return make_layout(B, H, n, b, g, w, r, need_bwd).total;
 }
 
-extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
-                                const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
-                                int H, int n, int d, int b, int g, int w, int r, float scale,
-                                int dtype, int global_mode, void* workspace,
-                                size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+// Both forward entry points: argument checks, work decomposition, launches.  Allocates nothing.
+int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                  const int32_t* rand_idx, const uint8_t* key_padding_mask, int B, int H, int n,
+                  int d, int b, int g, int w, int r, float scale, int dtype, int global_mode,
+                  void* workspace, size_t workspace_bytes, void* hip_stream) {
   int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
   if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
@@ -175,6 +179,74 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
   // is sized for the fp32 decomposition, which never needs fewer slots)
   p.slots_per_bh = p.cmb_g_rows * p.cmb_g_n + p.cmb_s_rows * p.cmb_s_n;
   return bb::launch_fwd(p, dtype == BB_BF16, static_cast<hipStream_t>(hip_stream));
+}
+
+// Scratch memory of bigbird_attn_fwd_static: one array per GPU the library is loaded on, held
+// until the process ends.  On the host the name of a __device__ array is only a handle for
+// HIP_SYMBOL; the array's address on a device comes from hipGetSymbolAddress with that device
+// current, once per device, and that pointer is what the kernels get.
+constexpr size_t kStaticScratchBytes = BIGBIRD_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];  // [device], nullptr until the first call on that device
+
+int static_scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    fprintf(stderr, "bigbird: bigbird_attn_fwd_static: no usable current device (%s, device %d)\n",
+            hipGetErrorString(e), dev);
+    return BB_ERR_LAUNCH;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr) {
+      fprintf(stderr, "bigbird: bigbird_attn_fwd_static: hipGetSymbolAddress failed on device %d: %s\n", dev,
+              hipGetErrorString(e));
+      return BB_ERR_LAUNCH;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return BB_OK;
+}
+
+}  // namespace
+
+extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
+                                int H, int n, int d, int b, int g, int w, int r, float scale,
+                                int dtype, int global_mode, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  return attn_fwd_impl(Q, K, V, O, LSE, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r, scale, dtype,
+                       global_mode, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int bigbird_attn_fwd_static(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                       const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
+                                       int H, int n, int d, int b, int g, int w, int r, float scale,
+                                       int dtype, int global_mode, void* hip_stream) {
+  int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
+  if (st != BB_OK) return st;
+  const size_t need = make_layout(B, H, n, b, g, w, r, 0).fwd_total;
+  if (need > kStaticScratchBytes) {
+    fprintf(stderr,
+            "bigbird: bigbird_attn_fwd_static: these sizes need %zu bytes of scratch, the static buffer holds "
+            "%zu; use bigbird_attn_fwd with a workspace of bigbird_attn_workspace_bytes()\n",
+            need, kStaticScratchBytes);
+    return BB_ERR_WORKSPACE;
+  }
+  void* ptr = nullptr;
+  st = static_scratch_of_current_device(&ptr);
+  if (st != BB_OK) return st;
+  // Nothing in the buffer has to start at zero: every partial result a launch reads was written
+  // by that launch.
+  return attn_fwd_impl(Q, K, V, O, LSE, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r, scale, dtype,
+                       global_mode, ptr, kStaticScratchBytes, hip_stream);
 }
 
 extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
