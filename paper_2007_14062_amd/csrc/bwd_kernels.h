@@ -6,7 +6,8 @@
 
 namespace bb {
 
-constexpr int kMaxBwdBlocks = 1024;  // longest query-block list a key block can have (LDS list)
+constexpr int kMaxBwdBlocks = 256;  // longest query-block list a key block can have (LDS list): n <= 16 384,
+                                    // the longest sequence the backward is verified on in full
 
 struct BwdParams {
   const void* Q;

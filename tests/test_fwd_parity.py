@@ -219,7 +219,7 @@ def test_cfg5_long_sequence_sampled_rows():
 
 
 def test_maximum_length_sampled_rows():
-    """n = 65 536 (nb = 1024, the longest sequence the backward accepts): sixteen workgroups and
+    """n = 65 536 (nb = 1024): sixteen workgroups and
     a merge per global row, key lists built from a 3072-entry table row set; sampled rows."""
     wl = inp.Workload("max_len", B=1, H=2, n=65536, pattern_seed=21, data_seed=321)
     _sampled_parity(wl, n_bh=1)
