@@ -30,7 +30,6 @@ import json
 import os
 import re
 import statistics
-import subprocess
 import sys
 import time
 
@@ -232,18 +231,20 @@ def kernel_source_sha256() -> str:
 
 
 def device_clock_mhz():
-    """Current / maximum shader clock as rocm-smi reports it, or None (no such tool, no such field)."""
-    try:
-        out = subprocess.run(["rocm-smi", "--showclocks", "--json"], capture_output=True, text=True, timeout=20).stdout
-        data = json.loads(out)
-        card = next(iter(data.values()))
-        for k, v in card.items():
-            if "sclk" in k.lower():
-                m = re.search(r"(\d+)\s*Mhz", str(v), re.I)
-                if m:
-                    return float(m.group(1))
-    except Exception:
-        pass
+    """Shader clock level the driver reports as current right after the timed runs (sysfs,
+    pp_dpm_sclk, the starred line), or None.  Read from a file: a process that has initialised
+    the GPU starts no other program."""
+    import glob
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")):
+        try:
+            with open(path) as f:
+                for line in f:
+                    if "*" in line:
+                        m = re.search(r"(\d+)\s*Mhz", line, re.I)
+                        if m:
+                            return float(m.group(1))
+        except OSError:
+            continue
     return None
 
 

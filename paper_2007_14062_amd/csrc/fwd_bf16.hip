@@ -877,9 +877,11 @@ __device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t)
 }
 
 // One global query block by a whole workgroup: 16 key blocks per wave, the four waves' (m, l, O~)
-// merged in LDS.  A function of its own for the same reason.
-__device__ __attribute__((noinline)) void global_row_workgroup(const void* kernargs) {
-  const FwdParams p = params_from(kernargs);
+// merged in LDS.  Inlined into the kernel, as the branch taken by the die's first workgroups: a
+// real call would start by saving a hundred callee-saved vector registers to scratch memory
+// (11 MB of HBM writes per launch at the BERT-base size, measured) for a caller that has nothing
+// in them.
+__device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
   const WaveCtx w(p.c);
   const Sched sc(p);
   const StraightOffsets so(w.lane);
@@ -990,7 +992,7 @@ __global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2))
 void fwd_kernel_bf16(FwdParams p) {
   const Sched sc(p);
   if (sc.global_wg) {
-    if ((sc.wg / p.geo.g_wgs) * kXcd + sc.xcd < static_cast<unsigned>(p.BH)) global_row_workgroup(kernel_kernargs());
+    if ((sc.wg / p.geo.g_wgs) * kXcd + sc.xcd < static_cast<unsigned>(p.BH)) global_row_workgroup(p);
     return;
   }
   const WaveCtx w(p.c);
