@@ -516,7 +516,13 @@ __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, 
   bool row_global;
   item_coords(p, w, sc, t, it, list_lo, list_len, row_global);
   const int bi = it.bh / p.H, h = it.bh % p.H;
-  const bool fast_list = !row_global && !p.kmask && p.rand_idx && p.r > 0 && p.g + p.w + p.r <= 64;
+  // Non-global rows: the table row comes through the scalar data path and the list is made
+  // without a vector memory access.  A padding mask is then applied to the finished list, lane i
+  // looking at block i (one round trip to memory for the whole list) -- for rows of one slice,
+  // where dropping blocks afterwards cannot move a slice boundary.  Everything else takes the
+  // general builder.
+  const bool fast_list = !row_global && p.rand_idx && p.r > 0 &&
+                         p.g + p.w + p.r <= (p.kmask ? kGlobalWaveLen : 64);
   if (fast_list) {
     const int32_t* rrow = p.rand_idx + (static_cast<size_t>(h) * p.nb + it.j) * p.r;
     int rnd = -1;
@@ -539,9 +545,20 @@ __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, 
   it.kl = w.klist[lane & (kGlobalWaveLen - 1)];
   asm volatile("" ::: "memory");
   it.any_partial = false;
-  if (p.kmask)
-    for (int i = 0; i < it.cnt; ++i)
-      it.any_partial |= key_valid_bits(p.kmask, bi, p.n, __builtin_amdgcn_readlane(it.kl, i)) != ~0ull;
+  if (p.kmask) {
+    bool any_valid = false, any_padded = false;
+    if (lane < it.cnt) block_mask_flags(p.kmask, bi, p.n, it.kl, any_valid, any_padded);
+    if (fast_list) {
+      // drop the blocks without a valid key (the general builder has done that already)
+      const uint64_t m = __ballot(any_valid);
+      if (any_valid) w.klist[mask_rank(m)] = it.kl;
+      it.cnt = static_cast<int>(__popcll(m));
+      asm volatile("" ::: "memory");
+      it.kl = w.klist[lane & (kGlobalWaveLen - 1)];
+      asm volatile("" ::: "memory");
+    }
+    it.any_partial = __any(any_valid && any_padded);
+  }
   // all of these are wave uniform; saying so keeps them (and what is computed from them) in
   // scalar registers
   it.bh = __builtin_amdgcn_readfirstlane(it.bh);

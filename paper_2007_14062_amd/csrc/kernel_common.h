@@ -167,6 +167,24 @@ __device__ __forceinline__ bool block_has_valid_key(const uint8_t* kmask, int bi
   return any != 0;
 }
 
+// The 64 mask bytes of key block k of batch bi (a byte is a flag): is any key valid, is any padded?
+__device__ __forceinline__ void block_mask_flags(const uint8_t* kmask, int bi, int n, int k, bool& any_valid,
+                                                 bool& any_padded) {
+  const u32x4* p = reinterpret_cast<const u32x4*>(kmask + static_cast<size_t>(bi) * n + k * kBlk);
+  unsigned any = 0, zero_byte = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const u32x4 v = p[i];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      any |= v[e];
+      zero_byte |= (v[e] - 0x01010101u) & ~v[e] & 0x80808080u;  // some byte of v[e] is 0
+    }
+  }
+  any_valid = any != 0;
+  any_padded = zero_byte != 0;
+}
+
 // Key blocks attended by query block j of head h (App. D items 1-3 as a set
 // union, minus blocks without a valid key), slice `chunk` (see WorkItem) of the
 // ascending-by-candidate list: entries [lo, lo+len).  Every lane of the calling wave takes
