@@ -159,7 +159,8 @@ int bigbird_attn_fwd_static(const void* Q, const void* K, const void* V, void* O
  * reduction over the random-block scatter is atomic free (fixed summation order,
  * bit-reproducible).  Gradients of padded keys are exactly 0.
  * The workspace must have been sized with need_bwd != 0.
- * BB_ERR_UNSUPPORTED for dtype BB_F32 (not built) and for n / b > 256.
+ * dtype BB_BF16 (the tuned path) or BB_F32 (fp32 end to end, plain kernels: a correctness
+ * configuration).  BB_ERR_UNSUPPORTED for n / b > 256.
  */
 int bigbird_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
                      const float* LSE, const void* dO, float* dQ, float* dK, float* dV,

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libbigbird.so")
 
-SOURCES = ["api.hip", "fwd_kernels.hip", "fwd_bf16.hip", "bwd_kernels.hip", "pattern_host.cpp"]
+SOURCES = ["api.hip", "fwd_kernels.hip", "fwd_bf16.hip", "bwd_kernels.hip", "bwd_f32.hip", "pattern_host.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -259,7 +259,6 @@ extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, con
   if (st != BB_OK) return st;
   if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
   if (!(scale > 0.f) || !std::isfinite(scale)) return BB_ERR_UNSUPPORTED;
-  if (dtype == BB_F32) return BB_ERR_UNSUPPORTED;  // the fp32 backward is not built
   if (n / b > bb::kMaxBwdBlocks) return BB_ERR_UNSUPPORTED;
   if (B == 0 || H == 0) return BB_OK;
   if (!Q || !K || !V || !O || !LSE || !dO || !dQ || !dK || !dV) return BB_ERR_NULL;
@@ -292,5 +291,6 @@ extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, con
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   p.cq = (p.nb + bb::kChunk - 1) / bb::kChunk;
   p.kv_items_per_bh = g * p.cq + (p.nb - g);
+  if (dtype == BB_F32) return bb::launch_bwd_f32(p, static_cast<hipStream_t>(hip_stream));
   return bb::launch_bwd_bf16(p, static_cast<hipStream_t>(hip_stream));
 }

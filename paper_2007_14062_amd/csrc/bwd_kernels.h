@@ -38,5 +38,9 @@ struct BwdParams {
 // fixed-order reductions.
 int launch_bwd_bf16(const BwdParams& p, hipStream_t stream);
 
+// The same for fp32 tensors (Q, K, V, O, dO fp32): two plain kernels, one workgroup per query
+// block and per key block, no partial results (correctness configuration, not tuned).
+int launch_bwd_f32(const BwdParams& p, hipStream_t stream);
+
 }  // namespace bb
 #endif  // BB_BWD_KERNELS_H_

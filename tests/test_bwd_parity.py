@@ -210,16 +210,66 @@ def test_cfg3_shape_backward_with_padding_sampled_heads():
         assert (hK[bi][:, pad[bi]] == 0).all() and (hV[bi][:, pad[bi]] == 0).all()
 
 
-def test_fp32_backward_is_refused_not_faked():
+TOL_F32 = 1e-4
+
+
+def check_full_f32(t, rand_idx, b, g, w, scale, key_mask=None, mode=0, tag=""):
+    """fp32 tensors through forward + backward; max abs error of the gradients <= 1e-4."""
     torch = torch_mod()
-    t = inp.make_tensors(1, 1, 128, 64, 24, "f32", with_dO=True)
     Q, K, V = device_qkv(t, "f32")
     dO = device_tensor(t, "dO", "f32")
-    empty = torch.zeros((1, 2, 0), dtype=torch.int32, device="cuda:0")
-    O, LSE = bb.bigbird_attn_fwd(Q, K, V, empty, g=1, w=1, scale=0.125)
-    with pytest.raises(bb.BigBirdError) as e:
-        bb.bigbird_attn_bwd(Q, K, V, O, LSE, dO, empty, g=1, w=1, scale=0.125)
-    assert e.value.status == -6
+    ridx = torch.from_numpy(np.ascontiguousarray(rand_idx)).to("cuda:0")
+    km = None if key_mask is None else torch.from_numpy(key_mask).to("cuda:0")
+    O, LSE = bb.bigbird_attn_fwd(Q, K, V, ridx, g=g, w=w, scale=scale, key_padding_mask=km, global_mode=mode)
+    dQ, dK, dV = bb.bigbird_attn_bwd(Q, K, V, O, LSE, dO, ridx, g=g, w=w, scale=scale,
+                                     key_padding_mask=km, global_mode=mode)
+    torch.cuda.synchronize()
+    ref = oracle.attn_bwd(t["Q"], t["K"], t["V"], t["dO"], rand_idx, b, g, w, scale,
+                          key_mask=key_mask, global_mode=mode)
+    errs = [np.abs(to_host(x) - r).max() for x, r in zip((dQ, dK, dV), ref)]
+    print(f"{tag}: max|ddQ|={errs[0]:.3e} max|ddK|={errs[1]:.3e} max|ddV|={errs[2]:.3e}")
+    assert all(np.isfinite(to_host(x)).all() for x in (dQ, dK, dV)), tag
+    assert max(errs) <= TOL_F32, (tag, errs)
+    return dQ, dK, dV
+
+
+def test_fp32_backward_cfg1_shape():
+    wl = inp.WORKLOADS["cfg1_fp32_small"]
+    t = inp.make_tensors(wl.B, wl.H, wl.n, wl.d, wl.data_seed, "f32", with_dO=True)
+    ridx = bb.bigbird_make_rand_idx(wl.H, wl.n, wl.b, wl.g, wl.w, wl.r, wl.pattern_seed)
+    check_full_f32(t, ridx, wl.b, wl.g, wl.w, wl.scale, tag="fp32 bwd cfg1 shape")
+
+
+def test_fp32_backward_ragged_padding_and_long_lists():
+    # leading globals, ragged shape
+    B, H, n, g, w, r = 2, 3, 640, 3, 5, 2
+    t = inp.make_tensors(B, H, n, 64, 17, "f32", with_dO=True)
+    ridx = bb.bigbird_make_rand_idx(H, n, 64, g, w, r, 9, bb.BB_GLOBAL_LEADING)
+    check_full_f32(t, ridx, 64, g, w, 0.2, mode=bb.BB_GLOBAL_LEADING, tag="fp32 bwd ragged")
+    # padding: unaligned lengths, a hole, one sequence without any valid key
+    B, H, n, g, w, r = 3, 2, 1024, 2, 3, 3
+    t = inp.make_tensors(B, H, n, 64, 31, "f32", with_dO=True)
+    ridx = bb.bigbird_make_rand_idx(H, n, 64, g, w, r, 4)
+    km = np.ones((B, n), dtype=np.uint8)
+    km[0, 700:] = 0
+    km[0, 130:150] = 0
+    km[1, :] = 0
+    dQ, dK, dV = check_full_f32(t, ridx, 64, g, w, 0.125, key_mask=km, tag="fp32 bwd padding")
+    assert (to_host(dK)[0][:, 700:] == 0).all() and (to_host(dV)[1] == 0).all() and (to_host(dQ)[1] == 0).all()
+    # every row and every column attended by all 80 blocks (lists longer than one chunk of 64)
+    B, H, n = 1, 1, 5120
+    nb = n // 64
+    t = inp.make_tensors(B, H, n, 64, 18, "f32", with_dO=True)
+    empty = np.full((H, nb, 0), -1, dtype=np.int32)
+    check_full_f32(t, empty, 64, nb, 1, 0.125, tag="fp32 bwd full coverage (all global, 80 blocks)")
+
+
+@pytest.mark.parametrize("g,w,r", [(0, 1, 0), (1, 1, 0), (0, 3, 2), (2, 3, 0), (1, 7, 4)])
+def test_fp32_backward_degenerate_patterns(g, w, r):
+    B, H, n = 1, 2, 1024
+    t = inp.make_tensors(B, H, n, 64, 19, "f32", with_dO=True)
+    ridx = bb.bigbird_make_rand_idx(H, n, 64, g, w, r, 3)
+    check_full_f32(t, ridx, 64, g, w, 0.125, tag=f"fp32 bwd g{g} w{w} r{r}")
 
 
 def test_seeded_sweep_of_small_configurations():
