@@ -15,14 +15,20 @@ explicit edge list at the paper's figure sizes, central finite differences for
 the gradients.  What is NOT pinned is agreement with the authors' released
 code on points the paper leaves open (how random blocks are drawn, whether
 overlapping components are counted once): "parity unpinned" for those readings.
+The ETC construction (etc.py: extra global tokens in front of the sequence) is pinned in
+tests/test_oracle_etc_pins.py: against the ITC functions where the two constructions coincide,
+by an independent per-element loop, by row counts at the paper's ETC sizes, by closed forms and
+by finite differences.
 """
 from .pattern import (GLOBAL_FIRST_LAST, GLOBAL_LEADING, global_blocks, window_blocks,
                       make_rand_idx, validate_rand_idx, neighbour_blocks, dense_block_mask,
                       dense_mask, count_block_pairs, reverse_random_lists)
 from .attention import attn_fwd, attn_bwd, attn_fwd_rows
+from .etc import dense_mask_etc, attn_fwd_etc, attn_bwd_etc
 
 __all__ = [
     "GLOBAL_FIRST_LAST", "GLOBAL_LEADING", "global_blocks", "window_blocks", "make_rand_idx",
     "validate_rand_idx", "neighbour_blocks", "dense_block_mask", "dense_mask",
     "count_block_pairs", "reverse_random_lists", "attn_fwd", "attn_bwd", "attn_fwd_rows",
+    "dense_mask_etc", "attn_fwd_etc", "attn_bwd_etc",
 ]
