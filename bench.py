@@ -173,6 +173,50 @@ def forward_line(bb, torch, dev, name: str, batches: int):
             "oracle_check": {"max_abs_dO": err_o, "max_abs_dLSE": err_l}}
 
 
+def etc_forward_lines(bb, torch, dev, batches: int):
+    """Forward timings of the ETC construction (Sec. 2: extra global tokens in front) at b = 64, total
+    length 4096, 12 heads, window of 3 blocks, no random blocks: 256 global tokens (four leading
+    global blocks) and 230 (App. E's NaturalQ figure: the fourth block padded with a key mask,
+    which sends every item through the per-key masking path)."""
+    import oracle
+    out = []
+    B, H, n, b, w, scale = 4, 12, 4096, 64, 3, 0.125
+    for n_global in (256, 230):
+        g = (n_global + b - 1) // b
+        t = inp.make_tensors(B, H, n, 64, 150 + n_global, "bf16")
+        km_h = None
+        if g * b != n_global:
+            km_h = np.ones((B, n), dtype=np.uint8)
+            km_h[:, n_global:g * b] = 0
+        dv = {x: torch.from_numpy(t[x + "_bits"].view(np.int16)).to(dev).view(torch.bfloat16) for x in ("Q", "K", "V")}
+        km = None if km_h is None else torch.from_numpy(km_h).to(dev)
+        empty_h = np.full((H, n // b, 0), -1, dtype=np.int32)
+        empty = torch.zeros((H, n // b, 0), dtype=torch.int32, device=dev)
+        O = torch.empty_like(dv["Q"])
+        LSE = torch.empty((B, H, n), dtype=torch.float32, device=dev)
+        ws = torch.empty(max(bb.bigbird_attn_workspace_bytes(B, H, n, 64, b, g, w, 0), 256), dtype=torch.uint8, device=dev)
+        step = bb.prepare_attn_fwd(dv["Q"], dv["K"], dv["V"], empty, O, LSE, ws, g=g, w=w, scale=scale,
+                                   key_padding_mask=km, global_mode=bb.BB_GLOBAL_LEADING)
+        med, mn, _ = settled_ms(torch, (step,), batches)
+        rows = [0, 100, n_global - 1, g * b, g * b + 31, 2000, n - 1]
+        Or, Lr = oracle.attn_fwd_rows(t["Q"], t["K"], t["V"], empty_h, b, g, w, scale, B - 1, H - 1, rows,
+                                      key_mask=km_h, global_mode=oracle.GLOBAL_LEADING)
+        err_o = float(np.abs(O.float().cpu().numpy()[B - 1, H - 1, rows] - Or).max())
+        err_l = float(np.abs(LSE.cpu().numpy()[B - 1, H - 1, rows] - Lr).max())
+        if err_o > TOL["bf16"] or err_l > TOL["bf16"]:
+            raise SystemExit(f"bench: ETC n_global={n_global}: timed output does not match the oracle "
+                             f"(max|dO|={err_o:.3e}, max|dLSE|={err_l:.3e})")
+        kbv = None if km_h is None else km_h
+        pairs = bb.bigbird_count_block_pairs(empty_h, kbv, B, H, n, b, g, w, 0, bb.BB_GLOBAL_LEADING)
+        fl = useful_flops_fwd(pairs, b, 64)
+        out.append({"workload": f"etc_{n_global}_global_tokens", "n_global": n_global, "leading_global_blocks": g,
+                    "block_pairs_with_valid_keys": pairs, "ms_per_step_median": med, "ms_per_step_min": mn,
+                    "useful_tflops": fl / (med * 1e-3) / 1e12,
+                    "frac_of_mfma_peak": fl / (med * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS,
+                    "oracle_check": {"max_abs_dO": err_o, "max_abs_dLSE": err_l}})
+    return out
+
+
 def time_fwd_bwd(bb, torch, dev, batches: int):
     """Forward + backward on the cfg4 workload (B=2): ms per step and useful TFLOP/s.
 
@@ -368,6 +412,7 @@ def main():
                      "kernel": "bb::fwd_kernel_bf16 (the only kernel of a forward call at this size)"},
     }
     if not args.skip_other_workloads:
+        result["etc_forward"] = etc_forward_lines(bb, torch, dev, max(3, args.batches // 2))
         result["other_workloads_forward"] = [forward_line(bb, torch, dev, nm, max(3, args.batches // 2))
                                              for nm in ("cfg1_fp32_small", "cfg3_key_padding", "cfg5_long_seq")]
     if not args.skip_backward:
