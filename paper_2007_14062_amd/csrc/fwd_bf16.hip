@@ -292,9 +292,10 @@ __device__ __forceinline__ void unit_probs(const f32x16& s, float c, bf16x8 (&pb
     }
 }
 
-// issue order of one slot: eight times (one MFMA, [LDS reads,] two exponentials, their
-// conversion), the two small row-sum MFMAs after the fourth and the eighth; nothing moves across
-// the end of a slot
+// issue order of one slot: eight times (one MFMA, [LDS reads,] two exponentials), the two small
+// row-sum MFMAs after the fourth and the eighth; the multiplications, conversions and lane reads
+// fall where the scheduler puts them between those (pinning them too measured 1.5 % slower);
+// nothing moves across the end of a slot
 template <int DS_READS>
 __device__ __forceinline__ void pin_slot() {
 #pragma unroll
@@ -302,7 +303,6 @@ __device__ __forceinline__ void pin_slot() {
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     if (u * 2 < DS_READS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
     __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);  // two exponentials
-    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);  // the next two scalings, a conversion, a lane read for a tile address
     if (u == 3 || u == 7) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
   }
   __builtin_amdgcn_sched_barrier(0);
@@ -792,7 +792,8 @@ __device__ __forceinline__ void store_rows_bf16(const FwdParams& p, const WaveCt
     wait_lds_reads();  // after the second batch the K buffer may be refilled
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
-      *reinterpret_cast<u32x4*>(orow + ((half * 4 + ii) * 8 + (lane >> 3)) * kDim + (lane & 7) * 8) = ov[ii];
+      // (non-temporal: the output is not read again, and K and V need the L2: 0.5 us at cfg 2)
+      __builtin_nontemporal_store(ov[ii], reinterpret_cast<u32x4*>(orow + ((half * 4 + ii) * 8 + (lane >> 3)) * kDim + (lane & 7) * 8));
   }
 }
 
