@@ -172,10 +172,10 @@ def test_attn_bwd_host_checks_fire_before_any_launch():
     assert call(w=2) == -2
     assert call(dK=odd) == -2
     assert call(d=32) == -6
-    assert call(dtype=0) == -6                     # fp32 backward is not built: refused, not faked
+    assert call(dtype=0, ws=None) == -5            # the fp32 backward goes through the same checks
     assert call(dtype=9) == -4
     assert call(scale=-1.0) == -6
-    assert call(n=64 * 2048) == -6                 # more key blocks than the backward's list holds
+    assert call(n=64 * 257) == -6                  # more key blocks than the backward's list holds (256)
     assert call(ws=None) == -5
     assert call(ws_bytes=1024) == -5
     assert call(B=0) == 0
@@ -191,3 +191,40 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(1, 1, 0, dtype=torch.int32)
     with pytest.raises(ValueError):
         bb.bigbird_attn_fwd(Q, Q, Q, t, g=1, w=1, scale=1.0)
+
+
+def test_binding_validator_refuses_wrong_dtypes_and_shapes():
+    """The C side reads tensors through raw pointers: the one validator shared by the forward,
+    backward and prepare_* wrappers must refuse what would be misread (checked on CPU tensors: the
+    validator looks at shapes and dtypes only)."""
+    import torch
+    from paper_2007_14062_amd.binding import _check_attn_args as chk
+    B, H, n, d, b, r = 2, 3, 256, 64, 64, 2
+    Q = torch.zeros((B, H, n, d), dtype=torch.bfloat16)
+    ridx = torch.zeros((H, n // b, r), dtype=torch.int32)
+    km = torch.ones((B, n), dtype=torch.uint8)
+    lse = torch.zeros((B, H, n), dtype=torch.float32)
+    g32 = torch.zeros((B, H, n, d), dtype=torch.float32)
+    assert chk(Q, Q, Q, ridx, km, b, O=Q, LSE=lse, dO=Q, grads=(g32, g32, g32)) == (B, H, n, d, r)
+    assert chk(Q, Q, Q, None, None, b) == (B, H, n, d, 0)
+    bad = [
+        dict(K=Q.float()),                                   # K of another dtype
+        dict(V=Q[:, :, :128]),                               # V of another shape
+        dict(rand_idx=ridx.long()),                          # int64 table
+        dict(rand_idx=ridx[:, :2]),                          # table with too few rows
+        dict(key_padding_mask=km.bool()),                    # mask not uint8
+        dict(key_padding_mask=km[:, :128]),                  # mask of another length
+        dict(LSE=lse.double()),                              # float64 LSE
+        dict(LSE=lse[:, :, :128]),
+        dict(O=Q.float()),
+        dict(dO=Q.float()),
+        dict(grads=(g32.double(), g32, g32)),                # float64 gradient buffer
+        dict(grads=(g32, g32[:, :1], g32)),
+    ]
+    for kw in bad:
+        args = dict(Q=Q, K=Q, V=Q, rand_idx=ridx, key_padding_mask=km, b=b, O=Q, LSE=lse, dO=Q, grads=(g32, g32, g32))
+        args.update(kw)
+        with pytest.raises(ValueError):
+            chk(**args)
+    with pytest.raises(ValueError):
+        chk(Q[0], Q[0], Q[0], ridx, km, b)                   # Q not [B, H, n, d]
