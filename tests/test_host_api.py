@@ -228,3 +228,13 @@ def test_binding_validator_refuses_wrong_dtypes_and_shapes():
             chk(**args)
     with pytest.raises(ValueError):
         chk(Q[0], Q[0], Q[0], ridx, km, b)                   # Q not [B, H, n, d]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; any other --gpus value exits with a message and status 2."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
