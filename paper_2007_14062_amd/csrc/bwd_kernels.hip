@@ -395,6 +395,7 @@ void bwd_dkv_kernel(BwdParams p) {
         for (int t = 0; t < 2; ++t)
           s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa[t][ks], kb[ks], s[t], 0, 0, 0);
     }
+    bf16x8 pb[4], dsb[4];
     {
       bf16x8 da[2][4];
       so.read(dot, da);
@@ -403,28 +404,24 @@ void bwd_dkv_kernel(BwdParams p) {
 #pragma unroll
         for (int t = 0; t < 2; ++t)
           dp[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da[t][ks], vb[ks], dp[t], 0, 0, 0);
-    }
-    // P = 2^(S c - LSE_q log2e) (0 for a padded key), dS = P o (dP - D_q); q runs along the rows
+      // P = 2^(S c - LSE_q log2e) beside the dP MFMAs; q runs along the rows.  (A padded key's
+      // column is not set to 0 here: a lane's key only reaches that key's own columns of dK and
+      // dV, which are cleared at the end.)
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int q0 = t * 32 + acc_row(r4 * 4, hf);
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lq + q0);
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(lq + t * 32 + acc_row(r4 * 4, hf));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = r4 * 4 + e;
-          float pv = fast_exp2(__builtin_fmaf(s[t][r], c, -l4[e]));
-          pv = key_valid ? pv : 0.f;
-          s[t][r] = pv;
-          dp[t][r] = pv * dp[t][r];
+          for (int e = 0; e < 4; ++e) {
+            s[t][r4 * 4 + e] = fast_exp2(__builtin_fmaf(s[t][r4 * 4 + e], c, -l4[e]));
+          }
         }
-      }
-    bf16x8 pb[4], dsb[4];
-    pack_acc_bf16(s, pb);
-    pack_acc_bf16(dp, dsb);
+      pack_acc_bf16(s, pb);
+    }
 
-    // dV^T += dO^T P and dK^T += Q^T dS: rows = d, columns = keys, contraction over the 64 queries
+    // dV^T += dO^T P and dK^T += Q^T dS: rows = d, columns = keys, contraction over the 64 queries;
+    // dS = P o (dP - D_q) and its conversion beside the dV MFMAs
     {
       bf16x8 dta[2][4];
       to.read(dot, dta);
@@ -433,6 +430,11 @@ void bwd_dkv_kernel(BwdParams p) {
 #pragma unroll
         for (int dt = 0; dt < 2; ++dt)
           dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dta[dt][sg], pb[sg], dv[dt], 0, 0, 0);
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) dp[t][r] *= s[t][r];
+      pack_acc_bf16(dp, dsb);
     }
     {
       bf16x8 qta[2][4];
@@ -445,10 +447,14 @@ void bwd_dkv_kernel(BwdParams p) {
     }
   }
 
+  // gradients of a padded key are exactly 0 (selected, not multiplied: its K row may hold anything)
 #pragma unroll
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) dk[dt][r] *= p.scale;
+    for (int r = 0; r < 16; ++r) {
+      dk[dt][r] = key_valid ? dk[dt][r] * p.scale : 0.f;
+      dv[dt][r] = key_valid ? dv[dt][r] : 0.f;
+    }
   store_acc_rows(dk_dst, dk, hf);
   store_acc_rows(dv_dst, dv, hf);
 }
