@@ -19,16 +19,21 @@ The ETC construction (etc.py: extra global tokens in front of the sequence) is p
 tests/test_oracle_etc_pins.py: against the ITC functions where the two constructions coincide,
 by an independent per-element loop, by row counts at the paper's ETC sizes, by closed forms and
 by finite differences.
+Attention dropout (dropout.py: the keep mask is a counter-based function of seed, slice, query and
+key) is pinned in tests/test_oracle_dropout_pins.py; agreement with the authors' own dropout
+stream is "parity unpinned" (the paper fixes only the rate).
 """
 from .pattern import (GLOBAL_FIRST_LAST, GLOBAL_LEADING, global_blocks, window_blocks,
                       make_rand_idx, validate_rand_idx, neighbour_blocks, dense_block_mask,
                       dense_mask, count_block_pairs, reverse_random_lists)
 from .attention import attn_fwd, attn_bwd, attn_fwd_rows
 from .etc import dense_mask_etc, attn_fwd_etc, attn_bwd_etc
+from .dropout import attn_fwd_dropout, attn_bwd_dropout, keep_mask, dropout_threshold, dropout_scale
 
 __all__ = [
     "GLOBAL_FIRST_LAST", "GLOBAL_LEADING", "global_blocks", "window_blocks", "make_rand_idx",
     "validate_rand_idx", "neighbour_blocks", "dense_block_mask", "dense_mask",
     "count_block_pairs", "reverse_random_lists", "attn_fwd", "attn_bwd", "attn_fwd_rows",
     "dense_mask_etc", "attn_fwd_etc", "attn_bwd_etc",
+    "attn_fwd_dropout", "attn_bwd_dropout", "keep_mask", "dropout_threshold", "dropout_scale",
 ]
