@@ -169,6 +169,58 @@ int bigbird_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
                      float scale, int dtype, int global_mode,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Attention dropout (the paper names only the rate: "attention dropout 0.1", App. E.1
+ * hyper-parameter table).  Reading: after the row softmax of eq. (AT) every attended
+ * probability P_ij is kept with probability 1 - p and the kept ones are scaled by
+ * 1 / (1 - p), independently per (batch, head, query i, key j); LSE stays that of the
+ * undropped softmax:
+ *   O_i = sum_j M_ij / (1 - p) P_ij V_j.
+ * The keep mask M is a function of (seed, bh = batch * H + head, i, j) alone, so that the
+ * forward and the backward of one step, called with the same p_drop and seed, see the same
+ * mask.  Counter-based generator on 32-bit integers (arithmetic modulo 2^32):
+ *   mix(x):  x ^= x >> 16; x *= 0x7feb352d; x ^= x >> 15; x *= 0x846ca68b; x ^= x >> 16
+ *   rk(i)   = mix(seed_lo ^ mix(seed_hi ^ (bh * n + i)))
+ *   w(i, j) = mix(rk(i) ^ ((j >> 1) * 0x9E3779B9))
+ *   u(i, j) = bits 0..14 of w for even j, bits 16..30 for odd j
+ *   M_ij    = [ u(i, j) >= T ],  T = round(p_drop * 32768)
+ * so the rate realised is T / 32768 (0.100006 for 0.1) and the scale 32768 / (32768 - T).
+ * p_drop must lie in [0, 1) with T < 32768, else BB_ERR_SHAPE (checked before anything
+ * else); p_drop == 0 is the plain call, bit for bit.  Use a new seed for every step and layer.
+ *
+ * bigbird_attn_fwd_dropout: arguments, checks and outputs of bigbird_attn_fwd, plus p_drop and
+ * seed.  The bf16 path applies the mask on its per-item path (the one that also serves
+ * blocks with padded keys inside), not in the pipelined one: expect about half the
+ * throughput of the plain call.
+ */
+int bigbird_attn_fwd_dropout(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                             const int32_t* rand_idx, const uint8_t* key_padding_mask,
+                             int B, int H, int n, int d, int b, int g, int w, int r,
+                             float scale, int dtype, int global_mode,
+                             float p_drop, uint64_t seed,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Backward of bigbird_attn_fwd_dropout (same p_drop and seed; O and LSE from that call), mask
+ * held fixed:  dV = (M o P / (1-p))^T dO;  dP = M / (1-p) o (dO V^T);  D_i = sum_c dO_ic O_ic;
+ * dS = P o (dP - D);  dQ = scale dS K;  dK = scale dS^T Q.  Otherwise as bigbird_attn_bwd.
+ */
+int bigbird_attn_bwd_dropout(const void* Q, const void* K, const void* V, const void* O,
+                             const float* LSE, const void* dO, float* dQ, float* dK, float* dV,
+                             const int32_t* rand_idx, const uint8_t* key_padding_mask,
+                             int B, int H, int n, int d, int b, int g, int w, int r,
+                             float scale, int dtype, int global_mode,
+                             float p_drop, uint64_t seed,
+                             void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * The keep mask itself, on the host (integers only; what the kernels compute element by
+ * element): rows row0 .. row0 + nrows - 1 of slice bh, keep_host[nrows][n] bytes (1 = kept).
+ * scale_out (may be NULL) receives 32768 / (32768 - T).  BB_ERR_NULL, BB_ERR_SHAPE.
+ */
+int bigbird_dropout_keep_mask(uint8_t* keep_host, float* scale_out, float p_drop, uint64_t seed,
+                              int bh, int n, int row0, int nrows);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,12 +28,12 @@ from .pattern import (GLOBAL_FIRST_LAST, GLOBAL_LEADING, global_blocks, window_b
                       dense_mask, count_block_pairs, reverse_random_lists)
 from .attention import attn_fwd, attn_bwd, attn_fwd_rows
 from .etc import dense_mask_etc, attn_fwd_etc, attn_bwd_etc
-from .dropout import attn_fwd_dropout, attn_bwd_dropout, keep_mask, dropout_threshold, dropout_scale
+from .dropout import attn_fwd_dropout, attn_fwd_dropout_rows, attn_bwd_dropout, keep_mask, dropout_threshold, dropout_scale
 
 __all__ = [
     "GLOBAL_FIRST_LAST", "GLOBAL_LEADING", "global_blocks", "window_blocks", "make_rand_idx",
     "validate_rand_idx", "neighbour_blocks", "dense_block_mask", "dense_mask",
     "count_block_pairs", "reverse_random_lists", "attn_fwd", "attn_bwd", "attn_fwd_rows",
     "dense_mask_etc", "attn_fwd_etc", "attn_bwd_etc",
-    "attn_fwd_dropout", "attn_bwd_dropout", "keep_mask", "dropout_threshold", "dropout_scale",
+    "attn_fwd_dropout", "attn_fwd_dropout_rows", "attn_bwd_dropout", "keep_mask", "dropout_threshold", "dropout_scale",
 ]

@@ -108,6 +108,29 @@ def attn_fwd_dropout(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float, p:
     return O, LSE
 
 
+def attn_fwd_dropout_rows(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float, p: float,
+                          seed: int, bi: int, h: int, rows, key_mask=None,
+                          global_mode: int = GLOBAL_FIRST_LAST):
+    """The same outputs for selected query rows of one (batch, head): O [len(rows), d], LSE
+    [len(rows)].  Each row is the definition evaluated on its own (for sampling large problems)."""
+    from .pattern import neighbour_blocks
+    rows = np.asarray(rows, dtype=np.int64)
+    H = np.asarray(Q).shape[1]
+    Kf = np.asarray(K[bi, h], dtype=np.float64)
+    Vf = np.asarray(V[bi, h], dtype=np.float64)
+    Qf = np.asarray(Q[bi, h][rows], dtype=np.float64)
+    n = Kf.shape[0]
+    A = np.zeros((len(rows), n), dtype=bool)
+    for t, i in enumerate(rows):
+        for k in neighbour_blocks(rand_idx[h], n // b, int(i) // b, g, w, global_mode):
+            A[t, k * b:(k + 1) * b] = True
+    if key_mask is not None:
+        A &= (np.asarray(key_mask[bi]) != 0)[None, :]
+    P, lse = _softmax_rows(scale * (Qf @ Kf.T), A)
+    M = keep_mask(seed, bi * H + h, n, p, rows=rows)
+    return (np.where(M, P, 0.0) * dropout_scale(p)) @ Vf, lse
+
+
 def attn_bwd_dropout(Q, K, V, dO, rand_idx, b: int, g: int, w: int, scale: float, p: float,
                      seed: int, key_mask=None, global_mode: int = GLOBAL_FIRST_LAST):
     """dQ, dK, dV [B,H,n,d] (fp64) of L = sum(O * dO) for the forward above, mask held fixed."""

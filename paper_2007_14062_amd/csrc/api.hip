@@ -88,11 +88,13 @@ extern "C" size_t bigbird_attn_workspace_bytes(int B, int H, int n, int d, int b
 
 namespace {
 
-// Both forward entry points: argument checks, work decomposition, launches.  Allocates nothing.
+const bb::Dropout kNoDropout = {0u, 0u, 0u, 1.0f};
+
+// The forward entry points: argument checks, work decomposition, launches.  Allocates nothing.
 int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* LSE,
                   const int32_t* rand_idx, const uint8_t* key_padding_mask, int B, int H, int n,
                   int d, int b, int g, int w, int r, float scale, int dtype, int global_mode,
-                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+                  const bb::Dropout& drop, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
   if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
@@ -120,6 +122,7 @@ int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* L
   p.B = B; p.H = H; p.BH = B * H; p.n = n; p.nb = n / b;
   p.g = g; p.w = w; p.r = r; p.global_mode = global_mode;
   p.c = scale * bb::kLog2e;
+  p.drop = drop;
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   if (dtype == BB_BF16) {
     bb::Bf16Geom& q = p.geo;
@@ -223,7 +226,33 @@ extern "C" int bigbird_attn_fwd(const void* Q, const void* K, const void* V, voi
                                 int dtype, int global_mode, void* workspace,
                                 size_t workspace_bytes, void* hip_stream) {
   return attn_fwd_impl(Q, K, V, O, LSE, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r, scale, dtype,
-                       global_mode, workspace, workspace_bytes, hip_stream);
+                       global_mode, kNoDropout, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int bigbird_attn_fwd_dropout(const void* Q, const void* K, const void* V, void* O, float* LSE,
+                                        const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
+                                        int H, int n, int d, int b, int g, int w, int r, float scale,
+                                        int dtype, int global_mode, float p_drop, uint64_t seed,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  bb::Dropout drop;
+  if (!bb::make_dropout(p_drop, seed, &drop)) return BB_ERR_SHAPE;
+  return attn_fwd_impl(Q, K, V, O, LSE, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r, scale, dtype,
+                       global_mode, drop, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int bigbird_dropout_keep_mask(uint8_t* keep_host, float* scale_out, float p_drop, uint64_t seed,
+                                         int bh, int n, int row0, int nrows) {
+  if (!keep_host) return BB_ERR_NULL;
+  if (bh < 0 || n <= 0 || row0 < 0 || nrows < 0 || row0 > n - nrows) return BB_ERR_SHAPE;
+  bb::Dropout drop;
+  if (!bb::make_dropout(p_drop, seed, &drop)) return BB_ERR_SHAPE;
+  if (scale_out) *scale_out = drop.rs;
+  for (int i = 0; i < nrows; ++i) {
+    const uint32_t rowid = static_cast<uint32_t>(bh) * static_cast<uint32_t>(n) + static_cast<uint32_t>(row0 + i);
+    for (int j = 0; j < n; ++j)
+      keep_host[static_cast<size_t>(i) * n + j] = bb::drop_keep(drop, rowid, static_cast<uint32_t>(j)) ? 1 : 0;
+  }
+  return BB_OK;
 }
 
 extern "C" int bigbird_attn_fwd_static(const void* Q, const void* K, const void* V, void* O, float* LSE,
@@ -246,15 +275,16 @@ extern "C" int bigbird_attn_fwd_static(const void* Q, const void* K, const void*
   // Nothing in the buffer has to start at zero: every partial result a launch reads was written
   // by that launch.
   return attn_fwd_impl(Q, K, V, O, LSE, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r, scale, dtype,
-                       global_mode, ptr, kStaticScratchBytes, hip_stream);
+                       global_mode, kNoDropout, ptr, kStaticScratchBytes, hip_stream);
 }
 
-extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
-                                const float* LSE, const void* dO, float* dQ, float* dK, float* dV,
-                                const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
-                                int H, int n, int d, int b, int g, int w, int r, float scale,
-                                int dtype, int global_mode, void* workspace,
-                                size_t workspace_bytes, void* hip_stream) {
+namespace {
+int attn_bwd_impl(const void* Q, const void* K, const void* V, const void* O,
+                  const float* LSE, const void* dO, float* dQ, float* dK, float* dV,
+                  const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
+                  int H, int n, int d, int b, int g, int w, int r, float scale,
+                  int dtype, int global_mode, const bb::Dropout& drop, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
   int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
   if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
@@ -288,9 +318,33 @@ extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, con
   p.g = g; p.w = w; p.r = r; p.global_mode = global_mode;
   p.c = scale * bb::kLog2e;
   p.scale = scale;
+  p.drop = drop;
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   p.cq = (p.nb + bb::kChunk - 1) / bb::kChunk;
   p.kv_items_per_bh = g * p.cq + (p.nb - g);
   if (dtype == BB_F32) return bb::launch_bwd_f32(p, static_cast<hipStream_t>(hip_stream));
   return bb::launch_bwd_bf16(p, static_cast<hipStream_t>(hip_stream));
+}
+}  // namespace
+
+extern "C" int bigbird_attn_bwd(const void* Q, const void* K, const void* V, const void* O,
+                                const float* LSE, const void* dO, float* dQ, float* dK, float* dV,
+                                const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
+                                int H, int n, int d, int b, int g, int w, int r, float scale,
+                                int dtype, int global_mode, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  return attn_bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r,
+                       scale, dtype, global_mode, kNoDropout, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" int bigbird_attn_bwd_dropout(const void* Q, const void* K, const void* V, const void* O,
+                                        const float* LSE, const void* dO, float* dQ, float* dK, float* dV,
+                                        const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
+                                        int H, int n, int d, int b, int g, int w, int r, float scale,
+                                        int dtype, int global_mode, float p_drop, uint64_t seed,
+                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+  bb::Dropout drop;
+  if (!bb::make_dropout(p_drop, seed, &drop)) return BB_ERR_SHAPE;
+  return attn_bwd_impl(Q, K, V, O, LSE, dO, dQ, dK, dV, rand_idx, key_padding_mask, B, H, n, d, b, g, w, r,
+                       scale, dtype, global_mode, drop, workspace, workspace_bytes, hip_stream);
 }

@@ -86,6 +86,8 @@ __global__ __launch_bounds__(kF32Threads) void bwd_f32_dq_kernel(BwdParams p) {
   }
   const float c = p.c;
   const bool row_global = pat.is_global(j);
+  // attention dropout: dP = M / (1 - p) o (dO V^T), M this row of the keep mask
+  const uint32_t drop_rk = p.drop.thr ? drop_row_key(p.drop, static_cast<uint32_t>(qrow)) : 0u;
 
   for (int lo = 0;; lo += kListChunk) {
     __syncthreads();  // the previous chunk's list and tiles are no longer read
@@ -107,7 +109,13 @@ __global__ __launch_bounds__(kF32Threads) void bwd_f32_dq_kernel(BwdParams p) {
         const bool valid = !p.kmask || p.kmask[static_cast<size_t>(bi) * p.n + kb * kBlk + kk] != 0;
         const float* krow = lds_k + kk * kTileStride;
         const float s = dot_row(q, krow);
-        const float dp = dot_row(go, lds_v + kk * kTileStride);
+        float dp = dot_row(go, lds_v + kk * kTileStride);
+        if (p.drop.thr) {
+          const uint32_t key = static_cast<uint32_t>(kb * kBlk + kk);
+          const uint32_t wd = drop_word(drop_rk, key >> 1);
+          const bool keep = (key & 1u) ? drop_keep_odd(wd, p.drop.thr) : drop_keep_even(wd, p.drop.thr);
+          dp = keep ? dp * p.drop.rs : 0.f;
+        }
         const float pr = valid ? fast_exp2(__builtin_fmaf(s, c, -lse2)) : 0.f;
         const float ds = pr * (dp - dsum);
 #pragma unroll
@@ -223,8 +231,13 @@ __global__ __launch_bounds__(kF32Threads) void bwd_f32_dkv_kernel(BwdParams p) {
         const float s = dot_row(kr, lds_q + i * kTileStride);
         const float dp = dot_row(vr, lds_do + i * kTileStride);
         const float pr = key_valid ? fast_exp2(__builtin_fmaf(s, c, -lds_lse[i])) : 0.f;
-        lds_p[i * (kBlk + 1) + kk] = pr;
-        lds_ds[i * (kBlk + 1) + kk] = pr * (dp - lds_d[i]);
+        // attention dropout: dV takes the kept, rescaled probabilities; dP is masked the same way
+        float mr = 1.f;
+        if (p.drop.thr)
+          mr = drop_keep(p.drop, static_cast<uint32_t>(jrow0 + i), static_cast<uint32_t>(k * kBlk + kk))
+                   ? p.drop.rs : 0.f;
+        lds_p[i * (kBlk + 1) + kk] = pr * mr;
+        lds_ds[i * (kBlk + 1) + kk] = pr * (dp * mr - lds_d[i]);
       }
       __syncthreads();
       for (int i = 0; i < kBlk; ++i) {

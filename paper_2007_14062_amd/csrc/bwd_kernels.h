@@ -2,6 +2,7 @@
 #ifndef BB_BWD_KERNELS_H_
 #define BB_BWD_KERNELS_H_
 
+#include "dropout.h"
 #include "kernel_common.h"
 
 namespace bb {
@@ -32,6 +33,7 @@ struct BwdParams {
   RowSplit split;  // query-row decomposition (dQ kernel), as in the forward
   int cq;          // slices of the query-block list of a global key block: ceil(nb / 8)
   int kv_items_per_bh;  // g*cq + (nb - g)
+  Dropout drop;    // attention dropout of the forward these gradients belong to (thr == 0: none)
 };
 
 // Enqueues: the dQ kernel (which also computes the row sums D), the dK/dV kernel and the

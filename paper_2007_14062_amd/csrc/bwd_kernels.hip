@@ -52,6 +52,9 @@ __device__ __forceinline__ void store_acc_rows(float* dst_row, const f32x16 (&a)
 // ---------------------------------------------------------------------------------------
 // dQ: one work item = (batch*head, query block j, slice of <= 8 key blocks of j's list)
 // ---------------------------------------------------------------------------------------
+// kDrop: attention dropout, dP = M / (1 - p) o (dO V^T) with M the keep mask (a second instance of
+// the kernel, so that the one without dropout keeps its registers and its schedule).
+template <bool kDrop>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void bwd_dq_kernel(BwdParams p) {
   __shared__ __attribute__((aligned(1024))) char lds_k[2 * kTile];
@@ -132,7 +135,9 @@ void bwd_dq_kernel(BwdParams p) {
   const float c = p.c;
   f32x16 neg_d;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) neg_d[r] = -dsum;
+  for (int r = 0; r < 16; ++r) neg_d[r] = kDrop ? 0.f : -dsum;  // (with dropout D is subtracted after the mask)
+  uint32_t drop_rk = 0u;
+  if constexpr (kDrop) drop_rk = drop_row_key(p.drop, static_cast<uint32_t>(qrow));
 
   for (int i = 0; i < cnt; ++i) {
     const int buf = i & 1;
@@ -193,6 +198,19 @@ void bwd_dq_kernel(BwdParams p) {
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x402, 8, 0);
     }
+    if constexpr (kDrop) {
+      // registers r, r + 1 are keys 2m, 2m + 1: one word of the mask
+      const float rs = p.drop.rs, nd = -dsum;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const uint32_t key = static_cast<uint32_t>(kb * kBlk + t * 32 + acc_row(r, hf));
+          const uint32_t wd = drop_word(drop_rk, key >> 1);
+          dp[t][r] = drop_keep_even(wd, p.drop.thr) ? __builtin_fmaf(dp[t][r], rs, nd) : nd;
+          dp[t][r + 1] = drop_keep_odd(wd, p.drop.thr) ? __builtin_fmaf(dp[t][r + 1], rs, nd) : nd;
+        }
+    }
     // dS^T = P^T o (dP^T - D)
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -226,8 +244,13 @@ void bwd_dq_kernel(BwdParams p) {
 // ---------------------------------------------------------------------------------------
 // dK, dV: one work item = (batch*head, key block k[, slice of its query-block list])
 // ---------------------------------------------------------------------------------------
+// kDrop: attention dropout (see bwd_dq_kernel): dV takes the kept probabilities (rescaled at the
+// end), dP is masked and rescaled before D is subtracted.  The row keys of the mask for the 64
+// queries of a list entry are staged in LDS beside LSE and D.
+template <bool kDrop>
 __global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void bwd_dkv_kernel(BwdParams p) {
+  __shared__ __attribute__((aligned(256))) uint32_t lds_rk[kDrop ? 2 * kBlk : 4];
   __shared__ __attribute__((aligned(1024))) char lds_q[2 * kTile];
   __shared__ __attribute__((aligned(1024))) char lds_do[2 * kTile];
   __shared__ __attribute__((aligned(256))) float lds_lse[2 * kBlk];
@@ -341,6 +364,10 @@ void bwd_dkv_kernel(BwdParams p) {
       vec_load_async(lbase + static_cast<size_t>(j) * kBlk, lds_lse_a + buf * (kBlk * 4), lane);
     else
       vec_load_async(dbase + static_cast<size_t>(j) * kBlk, lds_d_a + buf * (kBlk * 4), lane);
+    if constexpr (kDrop) {
+      if (wv == 0)
+        lds_rk[buf * kBlk + lane] = drop_row_key(p.drop, static_cast<uint32_t>(bh_row0 + static_cast<size_t>(j) * kBlk + lane));
+    }
   };
   if (cnt > 0) stage(0, 0);
 
@@ -384,7 +411,7 @@ void bwd_dkv_kernel(BwdParams p) {
       for (int r4 = 0; r4 < 4; ++r4) {
         const f32x4 d4 = *reinterpret_cast<const f32x4*>(dq + t * 32 + acc_row(r4 * 4, hf));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dp[t][r4 * 4 + e] = d4[e];
+        for (int e = 0; e < 4; ++e) dp[t][r4 * 4 + e] = kDrop ? 0.f : d4[e];
       }
     {
       bf16x8 qa[2][4];
@@ -417,7 +444,32 @@ void bwd_dkv_kernel(BwdParams p) {
             s[t][r4 * 4 + e] = fast_exp2(__builtin_fmaf(s[t][r4 * 4 + e], c, -l4[e]));
           }
         }
-      pack_acc_bf16(s, pb);
+      if constexpr (kDrop) {
+        // this lane's key against the 32 queries of its accumulator rows: the kept probabilities
+        // go to dV, and dP becomes M / (1 - p) o dP - D  (the staged vector holds -D)
+        const uint32_t* rkq = lds_rk + buf * kBlk;
+        const uint32_t my_pair = static_cast<uint32_t>(k * kBlk + wv * 32 + col) >> 1;
+        const uint32_t my_shift = (col & 1) ? 16u : 0u;
+        const float rs = p.drop.rs;
+        f32x16 sk[2];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r4 = 0; r4 < 4; ++r4) {
+            const u32x4 k4 = *reinterpret_cast<const u32x4*>(rkq + t * 32 + acc_row(r4 * 4, hf));
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(dq + t * 32 + acc_row(r4 * 4, hf));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              const uint32_t wd = drop_word(k4[e], my_pair);
+              const bool keep = ((wd >> my_shift) & 0x7fffu) >= p.drop.thr;
+              sk[t][r4 * 4 + e] = keep ? s[t][r4 * 4 + e] : 0.f;
+              dp[t][r4 * 4 + e] = keep ? __builtin_fmaf(dp[t][r4 * 4 + e], rs, d4[e]) : d4[e];
+            }
+          }
+        pack_acc_bf16(sk, pb);
+      } else {
+        pack_acc_bf16(s, pb);
+      }
     }
 
     // dV^T += dO^T P and dK^T += Q^T dS: rows = d, columns = keys, contraction over the 64 queries;
@@ -453,7 +505,7 @@ void bwd_dkv_kernel(BwdParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       dk[dt][r] = key_valid ? dk[dt][r] * p.scale : 0.f;
-      dv[dt][r] = key_valid ? dv[dt][r] : 0.f;
+      dv[dt][r] = key_valid ? (kDrop ? dv[dt][r] * p.drop.rs : dv[dt][r]) : 0.f;
     }
   store_acc_rows(dk_dst, dk, hf);
   store_acc_rows(dv_dst, dv, hf);
@@ -533,10 +585,17 @@ bool launch_failed(const char* what) {
 int launch_bwd_bf16(const BwdParams& p, hipStream_t stream) {
   const RowSplit& s = p.split;
   const unsigned qgrid = static_cast<unsigned>(kXcd) * s.bh_rounds * s.items_per_bh;
-  hipLaunchKernelGGL(bwd_dq_kernel, dim3(qgrid), dim3(kThreads), 0, stream, p);
+  const bool drop = p.drop.thr != 0;
+  if (drop)
+    hipLaunchKernelGGL(bwd_dq_kernel<true>, dim3(qgrid), dim3(kThreads), 0, stream, p);
+  else
+    hipLaunchKernelGGL(bwd_dq_kernel<false>, dim3(qgrid), dim3(kThreads), 0, stream, p);
   if (launch_failed("bwd_dq_kernel")) return BB_ERR_LAUNCH;
   const unsigned kvgrid = static_cast<unsigned>(kXcd) * s.bh_rounds * p.kv_items_per_bh;
-  hipLaunchKernelGGL(bwd_dkv_kernel, dim3(kvgrid), dim3(kThreads), 0, stream, p);
+  if (drop)
+    hipLaunchKernelGGL(bwd_dkv_kernel<true>, dim3(kvgrid), dim3(kThreads), 0, stream, p);
+  else
+    hipLaunchKernelGGL(bwd_dkv_kernel<false>, dim3(kvgrid), dim3(kThreads), 0, stream, p);
   if (launch_failed("bwd_dkv_kernel")) return BB_ERR_LAUNCH;
 
   // one reduction launch for the split dQ rows and the split dK / dV columns

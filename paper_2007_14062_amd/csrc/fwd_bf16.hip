@@ -544,7 +544,7 @@ __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, 
   asm volatile("" ::: "memory");
   it.kl = w.klist[lane & (kGlobalWaveLen - 1)];
   asm volatile("" ::: "memory");
-  it.any_partial = false;
+  it.any_partial = p.drop.thr != 0;  // attention dropout is applied on the slow path only
   if (p.kmask) {
     bool any_valid = false, any_padded = false;
     if (lane < it.cnt) block_mask_flags(p.kmask, bi, p.n, it.kl, any_valid, any_padded);
@@ -557,7 +557,7 @@ __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, 
       it.kl = w.klist[lane & (kGlobalWaveLen - 1)];
       asm volatile("" ::: "memory");
     }
-    it.any_partial = __any(any_valid && any_padded);
+    it.any_partial |= __any(any_valid && any_padded) != 0;
   }
   // all of these are wave uniform; saying so keeps them (and what is computed from them) in
   // scalar registers
@@ -697,9 +697,18 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
     m_ref[q] = neg_inf();
     l_run[q] = 0.f;
   }
+  // attention dropout (all items of a call with dropout come here): the keys of this lane's two
+  // rows of the keep mask
+  uint32_t drop_rk[2] = {0u, 0u};
+  if (p.drop.thr) {
+    const uint32_t row0 = static_cast<uint32_t>(item.bh) * static_cast<uint32_t>(p.n) + item.j * kBlk + (lane_id() & 31);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) drop_rk[q] = drop_row_key(p.drop, row0 + q * 32);
+  }
   for (int i = 0; i < item.cnt; ++i) {
+    const int kblock = __builtin_amdgcn_readlane(item.kl, i);
     uint64_t vbits = ~0ull;
-    if (p.kmask) vbits = key_valid_bits(p.kmask, item.bh / p.H, p.n, __builtin_amdgcn_readlane(item.kl, i));
+    if (p.kmask) vbits = key_valid_bits(p.kmask, item.bh / p.H, p.n, kblock);
     const char* kt = it.ktile(i);
     const char* vt = it.vtile(i);
     half_load_async(kt, cx.lds_k_a, 0, cx.voff);
@@ -747,10 +756,17 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
           for (int kk = 0; kk < 8; kk += 2) {
             const int r = sgl * 8 + kk;
             const float p0 = fast_exp2(s[t][r] - m_use), p1 = fast_exp2(s[t][r + 1] - m_use);
-            const bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+            bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
+            l_run[q] += p0 + p1;  // (the row sums are those of the undropped probabilities)
+            if (p.drop.thr) {
+              // registers r, r + 1 are keys 2m, 2m + 1: one word of the mask
+              const uint32_t key = static_cast<uint32_t>(kblock * kBlk + t * 32 + acc_row(r, cx.hf));
+              const uint32_t wd = drop_word(drop_rk[q], key >> 1);
+              if (!drop_keep_even(wd, p.drop.thr)) pk[0] = static_cast<__bf16>(0.f);
+              if (!drop_keep_odd(wd, p.drop.thr)) pk[1] = static_cast<__bf16>(0.f);
+            }
             pb[sgl][kk] = pk[0];
             pb[sgl][kk + 1] = pk[1];
-            l_run[q] += p0 + p1;
           }
         unit_pv(va[t], pb, o[q]);
       }
@@ -885,7 +901,7 @@ __device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t)
     float inv[2], lse[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      inv[q] = l_tot[q] > 0.f ? 1.f / l_tot[q] : 0.f;
+      inv[q] = l_tot[q] > 0.f ? p.drop.rs / l_tot[q] : 0.f;  // (rs: 1, or the dropout scale)
       lse[q] = l_tot[q] > 0.f ? (m_ref[q] + fast_log2(l_tot[q])) * kLn2 : neg_inf();
     }
     store_rows_bf16(p, w, it, o, inv, lse);
@@ -905,6 +921,9 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
   const StraightOffsets so(w.lane);
   const TransposedOffsets to(w.lane);
   const int lane = w.lane, wv = w.wv, hf = w.hf, col = w.col;
+#ifdef BB_STAMPS
+  const long long rt0 = __builtin_amdgcn_s_memrealtime();
+#endif
   Item cur;
   make_item(p, w, sc, 0, cur);
   bf16x8 qb[2][4], ka[2][4];
@@ -949,6 +968,15 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
       mrg_m[wv][q * 32 + col] = !(l_tot[q] > 0.f) ? neg_inf() : m_ref[q];
       mrg_l[wv][q * 32 + col] = l_tot[q];
     }
+#ifdef BB_STAMPS
+  if (lane == 0) {  // (nchunks == 1 only: the partial-result area is otherwise in use)
+    long long* dst = reinterpret_cast<long long*>(p.part_o) + (static_cast<size_t>(blockIdx.x) * kFwdWaves + wv) * 16;
+    dst[0] = rt0;
+    dst[1] = __builtin_amdgcn_s_memrealtime();
+    dst[2] = -1;
+    dst[15] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));  // HW_ID: where the wave ran
+  }
+#endif
   __syncthreads();  // all four waves of a global workgroup arrive here
   // wave w now owns query rows 16w .. 16w+15; a lane owns 16 d columns of one row
   const size_t row_blk = static_cast<size_t>(cur.bh) * p.n + cur.j * kBlk;
@@ -977,7 +1005,7 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
   }
   const size_t row = row_blk + q;
   if (cur.nchunks == 1) {
-    const float inv = L > 0.f ? 1.f / L : 0.f;
+    const float inv = L > 0.f ? p.drop.rs / L : 0.f;  // (rs: 1, or the dropout scale)
     if (part == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
     bf16x8 v0, v1;
 #pragma unroll
@@ -1231,6 +1259,7 @@ void fwd_kernel_bf16(FwdParams p) {
     dst[10] = st_t[0];
     dst[11] = st_t[1];
     dst[12] = st_t[2];
+    dst[15] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));  // HW_ID: where the wave ran
   }
 #endif
 

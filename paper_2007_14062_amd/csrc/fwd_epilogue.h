@@ -14,7 +14,7 @@ __device__ __forceinline__ void fwd_store(const FwdParams& p, const WorkItem& it
                                           float m_ref, float l_tot, float c, size_t qrow, int qi,
                                           int hf) {
   if (it.nchunks == 1) {
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    const float inv = l_tot > 0.f ? p.drop.rs / l_tot : 0.f;  // (rs: 1, or the dropout scale)
     if (hf == 0)
       p.LSE[qrow] = l_tot > 0.f ? (m_ref * c + fast_log2(l_tot)) * kLn2 : neg_inf();
 #pragma unroll

@@ -2,6 +2,7 @@
 #ifndef BB_FWD_KERNELS_H_
 #define BB_FWD_KERNELS_H_
 
+#include "dropout.h"
 #include "kernel_common.h"
 
 namespace bb {
@@ -42,6 +43,7 @@ struct FwdParams {
   // rows whose slices the merge kernel combines: cmb_g_rows global rows of cmb_g_n slices each
   // (slots first), then cmb_s_rows non-global rows of cmb_s_n slices; slots_per_bh in total
   int cmb_g_rows, cmb_g_n, cmb_s_rows, cmb_s_n, slots_per_bh;
+  Dropout drop;  // attention dropout (thr == 0: none)
 };
 
 // Enqueues the fused forward kernel and, if any row is split, the merge kernel.

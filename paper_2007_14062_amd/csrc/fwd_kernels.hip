@@ -80,6 +80,8 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel_f32(FwdParams p) {
   for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+  // attention dropout: the key of this lane's row of the keep mask
+  const uint32_t drop_rk = p.drop.thr ? drop_row_key(p.drop, static_cast<uint32_t>(qrow)) : 0u;
   float m_run = neg_inf();  // running maximum of the raw scores q.k (both halves agree)
   float l_run = 0.f;        // this lane's share of the running sum of 2^((q.k - m) c)
   const float c = p.c;
@@ -158,6 +160,20 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel_f32(FwdParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
 
+    // ---- attention dropout: the row sums above are those of the undropped probabilities; what
+    // multiplies V is the kept part (registers r, r+1 are keys 2m, 2m+1: one word of the mask)
+    if (p.drop.thr) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+          const uint32_t key = static_cast<uint32_t>(kb * kBlk + t * 32 + acc_row(r, hf));
+          const uint32_t wd = drop_word(drop_rk, key >> 1);
+          if (!drop_keep_even(wd, p.drop.thr)) s[t][r] = 0.f;
+          if (!drop_keep_odd(wd, p.drop.thr)) s[t][r + 1] = 0.f;
+        }
+    }
+
     // ---- O^T += V^T P^T: the S^T accumulator is the B operand as it stands; slot hf of
     // register r is key 32t + acc_row(r, hf), and V is read in that same key order.
     const float* vbase = reinterpret_cast<const float*>(lds_v);
@@ -230,7 +246,7 @@ __global__ __launch_bounds__(kCombineThreads) void fwd_combine_kernel(FwdParams 
       }
     }
   }
-  const float inv = L > 0.f ? 1.f / L : 0.f;
+  const float inv = L > 0.f ? p.drop.rs / L : 0.f;  // (rs: 1, or the dropout scale)
   const size_t row = static_cast<size_t>(bh) * p.n + j * kBlk + q;
   if ((threadIdx.x & 15) == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
   if constexpr (BF16) {

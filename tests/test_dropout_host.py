@@ -1,0 +1,40 @@
+"""Host-side checks of the dropout entry points (no GPU): the library's keep-mask generator
+against the oracle's, integer for integer, and the argument checks that fire before any launch."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import paper_2007_14062_amd as bb
+from oracle.dropout import dropout_scale, keep_mask
+
+
+@pytest.mark.parametrize("p,seed,bh,n", [(0.1, 1234567890123456789, 0, 128), (0.37, 5, 77, 192),
+                                         (0.0, 9, 3, 64), (0.9, 2 ** 64 - 1, 1000, 256),
+                                         (0.5, 0, 4_000_000, 2048)])
+def test_library_mask_equals_oracle_mask(p, seed, bh, n):
+    rows = min(n, 96)
+    row0 = n - rows
+    m, s = bb.bigbird_dropout_keep_mask(p, seed, bh, n, row0=row0, nrows=rows)
+    want = keep_mask(seed, bh, n, p, rows=np.arange(row0, n))
+    assert (m.astype(bool) == want).all()
+    assert abs(s - dropout_scale(p)) <= 1e-6 * s
+
+
+def test_bad_rates_and_ranges_are_refused():
+    lib = bb.load_library()
+    out = np.zeros((4, 64), dtype=np.uint8)
+    ptr = out.ctypes.data_as(ctypes.c_void_p)
+    for p in (-0.1, 1.0, 2.0, float("nan"), 0.99999):
+        assert lib.bigbird_dropout_keep_mask(ptr, None, p, 1, 0, 64, 0, 4) == -2
+    assert lib.bigbird_dropout_keep_mask(None, None, 0.1, 1, 0, 64, 0, 4) == -1
+    assert lib.bigbird_dropout_keep_mask(ptr, None, 0.1, 1, 0, 64, 62, 4) == -2
+    assert lib.bigbird_dropout_keep_mask(ptr, None, 0.1, 1, -1, 64, 0, 4) == -2
+    # the attention calls check the rate before anything else: no pointer is touched
+    z = ctypes.c_void_p(0)
+    args_f = [z] * 7 + [1, 1, 64, 64, 64, 0, 1, 0, ctypes.c_float(1.0), 1, 0]
+    assert lib.bigbird_attn_fwd_dropout(*args_f, ctypes.c_float(1.5), 1, z, 0, z) == -2
+    args_b = [z] * 11 + [1, 1, 64, 64, 64, 0, 1, 0, ctypes.c_float(1.0), 1, 0]
+    assert lib.bigbird_attn_bwd_dropout(*args_b, ctypes.c_float(-0.5), 1, z, 0, z) == -2
+    # a valid rate goes on to the usual checks (NULL tensors)
+    assert lib.bigbird_attn_fwd_dropout(*args_f, ctypes.c_float(0.1), 1, z, 0, z) == -1

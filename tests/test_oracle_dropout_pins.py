@@ -193,6 +193,20 @@ def test_gradients_by_finite_differences_with_the_mask_fixed():
     assert (dK[0, :, 21:] == 0).all() and (dV[0, :, 21:] == 0).all()
 
 
+def test_sampled_rows_equal_the_full_evaluation():
+    from oracle.dropout import attn_fwd_dropout_rows
+    B, H, n, d, b, g, w, r = 2, 3, 48, 4, 4, 2, 3, 2
+    ridx = oracle.make_rand_idx(H, n, b, g, w, r, 6)
+    Q, K, V = (_rand((B, H, n, d), s) for s in (31, 32, 33))
+    km = np.ones((B, n), dtype=np.uint8)
+    km[1, 37:] = 0
+    O, L = attn_fwd_dropout(Q, K, V, ridx, b, g, w, 0.3, 0.2, 99, key_mask=km)
+    rows = [0, 5, 17, 46, 47]
+    for bi, h in ((0, 0), (1, 2)):
+        Or, Lr = attn_fwd_dropout_rows(Q, K, V, ridx, b, g, w, 0.3, 0.2, 99, bi, h, rows, key_mask=km)
+        assert np.abs(Or - O[bi, h][rows]).max() < 1e-13 and np.abs(Lr - L[bi, h][rows]).max() < 1e-13
+
+
 def test_row_sums_of_p_dp_equal_do_dot_o():
     B, H, n, d, b, g, w, r = 1, 1, 32, 5, 4, 2, 3, 1
     p, seed, scale = 0.4, 5, 0.7
