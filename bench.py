@@ -225,7 +225,7 @@ def time_fwd_bwd(bb, torch, dev, batches: int):
     """
     wl = inp.WORKLOADS["cfg4_fwd_bwd"]
     rand_idx = bb.bigbird_make_rand_idx(wl.H, wl.n, wl.b, wl.g, wl.w, wl.r, wl.pattern_seed)
-    _, dv = device_inputs(wl, torch, dev)
+    t, dv = device_inputs(wl, torch, dev)
     ridx = torch.from_numpy(rand_idx).to(dev)
     pairs = bb.bigbird_count_block_pairs(rand_idx, None, wl.B, wl.H, wl.n, wl.b, wl.g, wl.w, wl.r)
     O = torch.empty_like(dv["Q"])
@@ -244,6 +244,35 @@ def time_fwd_bwd(bb, torch, dev, batches: int):
         out[name] = {"ms_per_step_median": med, "ms_per_step_min": mn,
                      "useful_tflops": fl / (med * 1e-3) / 1e12,
                      "pct_of_bf16_mfma_peak": 100.0 * fl / (med * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+    # the same step with attention dropout 0.1 (App. E.1): the bf16 forward then runs its per-item
+    # path; the outputs of the timed calls are checked against the dropout oracle on sampled rows
+    p_drop, seed = 0.1, 20200728
+    fwd_d = bb.prepare_attn_fwd(dv["Q"], dv["K"], dv["V"], ridx, O, LSE, ws, g=wl.g, w=wl.w, scale=wl.scale,
+                                p_drop=p_drop, seed=seed)
+    bwd_d = bb.prepare_attn_bwd(dv["Q"], dv["K"], dv["V"], O, LSE, dv["dO"], ridx, *grads, ws,
+                                g=wl.g, w=wl.w, scale=wl.scale, p_drop=p_drop, seed=seed)
+    drop = {"p_drop": p_drop}
+    for name, fns, mult in (("forward", (fwd_d,), 4.0), ("backward", (bwd_d,), 10.0),
+                            ("forward_backward", (fwd_d, bwd_d), 14.0)):
+        med, mn, _ = settled_ms(torch, fns, batches)
+        fl = mult * wl.b * wl.b * wl.d * pairs
+        drop[name] = {"ms_per_step_median": med, "ms_per_step_min": mn,
+                      "useful_tflops": fl / (med * 1e-3) / 1e12,
+                      "pct_of_bf16_mfma_peak": 100.0 * fl / (med * 1e-3) / 1e12 / BF16_MFMA_PEAK_TFLOPS}
+    import oracle
+    torch.cuda.synchronize()
+    Oh = O.float().cpu().numpy().astype(np.float64)
+    worst = 0.0
+    rng = np.random.default_rng(1)
+    for (bi, h) in ((0, 0), (wl.B - 1, wl.H - 1)):
+        rows = sorted({j * wl.b + o for j in (0, 1, wl.nb - 1, int(rng.integers(2, wl.nb - 2))) for o in (0, 33, wl.b - 1)})
+        Or, _ = oracle.attn_fwd_dropout_rows(t["Q"], t["K"], t["V"], rand_idx, wl.b, wl.g, wl.w, wl.scale,
+                                             p_drop, seed, bi, h, rows)
+        worst = max(worst, float(np.abs(Oh[bi, h, rows] - Or).max()))
+    if not worst <= 2e-2:
+        raise SystemExit(f"bench.py: dropout forward disagrees with the oracle: max|dO| = {worst:.3e}")
+    drop["oracle_check_max_abs_err_O"] = worst
+    out["dropout"] = drop
     out["workload"] = wl.name
     out["block_pairs"] = pairs
     return out
