@@ -14,7 +14,11 @@ Readings where the paper is silent:
   * a key-padding mask (never mentioned in the paper) removes keys for every
     query, global rows included; a row left without any key gives O = 0,
     LSE = -inf and zero gradients;
-  * LSE is the natural log of the sum of exp(scale * q.k) over N(i).
+  * LSE is the natural log of the sum of exp(scale * q.k) over N(i);
+  * optional (skip_padded_query_blocks): the same mask read as a query mask at block
+    granularity -- a query block in which every position is padded has no neighbours at all
+    (O = 0, LSE = -inf, no gradient through it), the way a caller that never reads padded
+    rows would want them; blocks with at least one valid position are unchanged.
 The backward pass is not in the paper; it is the calculus of the forward.
 """
 from __future__ import annotations
@@ -24,10 +28,14 @@ import numpy as np
 from .pattern import GLOBAL_FIRST_LAST, dense_mask
 
 
-def _adjacency(rand_idx_h, n, b, g, w, global_mode, key_valid_row):
+def _adjacency(rand_idx_h, n, b, g, w, global_mode, key_valid_row, skip_padded_query_blocks=False):
     A = dense_mask(rand_idx_h, n, b, g, w, global_mode)
     if key_valid_row is not None:
-        A = A & (np.asarray(key_valid_row) != 0)[None, :]
+        valid = np.asarray(key_valid_row) != 0
+        A = A & valid[None, :]
+        if skip_padded_query_blocks:
+            block_has_valid = valid.reshape(n // b, b).any(axis=1)
+            A = A & np.repeat(block_has_valid, b)[:, None]
     return A
 
 
@@ -46,7 +54,7 @@ def _softmax_rows(S: np.ndarray, A: np.ndarray):
 
 
 def attn_fwd(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float,
-             key_mask=None, global_mode: int = GLOBAL_FIRST_LAST):
+             key_mask=None, global_mode: int = GLOBAL_FIRST_LAST, skip_padded_query_blocks: bool = False):
     """O [B,H,n,d] and LSE [B,H,n] in fp64 for Q, K, V [B,H,n,d] (eq. (AT), per head).
 
     rand_idx is [H, n/b, r]; key_mask is None or [B, n] with non-zero = valid key.
@@ -60,7 +68,7 @@ def attn_fwd(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float,
     for bi in range(B):
         for h in range(H):
             A = _adjacency(rand_idx[h], n, b, g, w, global_mode,
-                           None if key_mask is None else key_mask[bi])
+                           None if key_mask is None else key_mask[bi], skip_padded_query_blocks)
             S = scale * (Q[bi, h] @ K[bi, h].T)
             P, lse = _softmax_rows(S, A)
             O[bi, h] = P @ V[bi, h]
@@ -69,7 +77,8 @@ def attn_fwd(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float,
 
 
 def attn_fwd_rows(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float, bi: int, h: int,
-                  rows, key_mask=None, global_mode: int = GLOBAL_FIRST_LAST):
+                  rows, key_mask=None, global_mode: int = GLOBAL_FIRST_LAST,
+                  skip_padded_query_blocks: bool = False):
     """The same outputs for selected query rows of one (batch, head): O [len(rows), d], LSE [len(rows)].
 
     Used to sample large problems; each row is the definition evaluated on its own.
@@ -86,14 +95,20 @@ def attn_fwd_rows(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float, bi: i
         for k in neighbour_blocks(rand_idx[h], nb, int(i) // b, g, w, global_mode):
             A[t, k * b:(k + 1) * b] = True
     if key_mask is not None:
-        A &= (np.asarray(key_mask[bi]) != 0)[None, :]
+        valid = np.asarray(key_mask[bi]) != 0
+        A &= valid[None, :]
+        if skip_padded_query_blocks:
+            for t, i in enumerate(rows):
+                j = int(i) // b
+                if not valid[j * b:(j + 1) * b].any():
+                    A[t, :] = False
     S = scale * (Qf @ Kf.T)
     P, lse = _softmax_rows(S, A)
     return P @ Vf, lse
 
 
 def attn_bwd(Q, K, V, dO, rand_idx, b: int, g: int, w: int, scale: float,
-             key_mask=None, global_mode: int = GLOBAL_FIRST_LAST):
+             key_mask=None, global_mode: int = GLOBAL_FIRST_LAST, skip_padded_query_blocks: bool = False):
     """Gradients dQ, dK, dV [B,H,n,d] (fp64) of L = sum(O * dO) w.r.t. Q, K, V.
 
     With P the row softmax:  dV = P^T dO;  dP = dO V^T;  D_i = sum_k P_ik dP_ik;
@@ -110,7 +125,7 @@ def attn_bwd(Q, K, V, dO, rand_idx, b: int, g: int, w: int, scale: float,
     for bi in range(B):
         for h in range(H):
             A = _adjacency(rand_idx[h], n, b, g, w, global_mode,
-                           None if key_mask is None else key_mask[bi])
+                           None if key_mask is None else key_mask[bi], skip_padded_query_blocks)
             S = scale * (Q[bi, h] @ K[bi, h].T)
             P, _ = _softmax_rows(S, A)
             dV[bi, h] = P.T @ dO[bi, h]

@@ -87,7 +87,7 @@ def keep_mask(seed: int, bh: int, n: int, p: float, rows=None) -> np.ndarray:
 
 
 def attn_fwd_dropout(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float, p: float, seed: int,
-                     key_mask=None, global_mode: int = GLOBAL_FIRST_LAST):
+                     key_mask=None, global_mode: int = GLOBAL_FIRST_LAST, skip_padded_query_blocks: bool = False):
     """O [B,H,n,d] with attention dropout, and the undropped LSE [B,H,n]; fp64."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -99,7 +99,7 @@ def attn_fwd_dropout(Q, K, V, rand_idx, b: int, g: int, w: int, scale: float, p:
     for bi in range(B):
         for h in range(H):
             A = _adjacency(rand_idx[h], n, b, g, w, global_mode,
-                           None if key_mask is None else key_mask[bi])
+                           None if key_mask is None else key_mask[bi], skip_padded_query_blocks)
             S = scale * (Q[bi, h] @ K[bi, h].T)
             P, lse = _softmax_rows(S, A)
             M = keep_mask(seed, bi * H + h, n, p)
@@ -132,7 +132,7 @@ def attn_fwd_dropout_rows(Q, K, V, rand_idx, b: int, g: int, w: int, scale: floa
 
 
 def attn_bwd_dropout(Q, K, V, dO, rand_idx, b: int, g: int, w: int, scale: float, p: float,
-                     seed: int, key_mask=None, global_mode: int = GLOBAL_FIRST_LAST):
+                     seed: int, key_mask=None, global_mode: int = GLOBAL_FIRST_LAST, skip_padded_query_blocks: bool = False):
     """dQ, dK, dV [B,H,n,d] (fp64) of L = sum(O * dO) for the forward above, mask held fixed."""
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
@@ -146,7 +146,7 @@ def attn_bwd_dropout(Q, K, V, dO, rand_idx, b: int, g: int, w: int, scale: float
     for bi in range(B):
         for h in range(H):
             A = _adjacency(rand_idx[h], n, b, g, w, global_mode,
-                           None if key_mask is None else key_mask[bi])
+                           None if key_mask is None else key_mask[bi], skip_padded_query_blocks)
             S = scale * (Q[bi, h] @ K[bi, h].T)
             P, _ = _softmax_rows(S, A)
             Mr = np.where(keep_mask(seed, bi * H + h, n, p), rs, 0.0)

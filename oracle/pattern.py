@@ -180,11 +180,13 @@ def dense_mask(rand_idx_h: np.ndarray, n: int, b: int, g: int, w: int,
 
 def count_block_pairs(rand_idx: np.ndarray, n: int, b: int, g: int, w: int,
                       global_mode: int = GLOBAL_FIRST_LAST,
-                      key_block_valid: np.ndarray | None = None) -> int:
+                      key_block_valid: np.ndarray | None = None,
+                      skip_padded_query_blocks: bool = False) -> int:
     """Number of (query block, key block) pairs in the pattern, summed over heads.
 
     With key_block_valid (bool [nb]) only pairs whose key block holds at least one
-    valid key are counted (the useful-work count under a key-padding mask).
+    valid key are counted (the useful-work count under a key-padding mask); with
+    skip_padded_query_blocks also only those whose query block holds a valid position.
     """
     nb = n // b
     total = 0
@@ -192,6 +194,8 @@ def count_block_pairs(rand_idx: np.ndarray, n: int, b: int, g: int, w: int,
         Mb = dense_block_mask(rand_idx[h], nb, g, w, global_mode)
         if key_block_valid is not None:
             Mb = Mb & np.asarray(key_block_valid, dtype=bool)[None, :]
+            if skip_padded_query_blocks:
+                Mb = Mb & np.asarray(key_block_valid, dtype=bool)[:, None]
         total += int(Mb.sum())
     return total
 
