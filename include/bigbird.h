@@ -59,6 +59,16 @@ enum { BB_F32 = 0, BB_BF16 = 1 };
  * blocks; LEADING: blocks 0 .. g-1. */
 enum { BB_GLOBAL_FIRST_LAST = 0, BB_GLOBAL_LEADING = 1 };
 
+/* Option flag, OR-ed into the global_mode argument of the attention calls and of
+ * bigbird_count_block_pairs (the paper has no padding; this is a reading of the mask).  With
+ * it the key-padding mask is also read as a query mask, block by block: a query block in
+ * which every position is padded is not computed -- its rows get O = 0, LSE = -inf, send
+ * no gradient to K and V and receive dQ = 0 -- the way a caller that never reads padded rows
+ * wants them.  Query blocks with at least one valid position are computed in full, as
+ * without the flag.  Ignored when there is no mask.  Give the backward call the flag the
+ * forward call had. */
+enum { BB_SKIP_PADDED_QUERY_BLOCKS = 0x100 };
+
 /* Human-readable name of a status code.  Never NULL. */
 const char* bigbird_status_string(int status);
 

@@ -4,7 +4,8 @@ Thin Python binding over the C ABI of include/bigbird.h.  All computation runs i
 the HIP kernels of libbigbird.so; PyTorch only supplies device memory and streams.
 There is no CPU fallback: a missing library raises.
 """
-from .binding import (BB_BF16, BB_F32, BB_GLOBAL_FIRST_LAST, BB_GLOBAL_LEADING, BigBirdError,
+from .binding import (BB_BF16, BB_F32, BB_GLOBAL_FIRST_LAST, BB_GLOBAL_LEADING,
+                      BB_SKIP_PADDED_QUERY_BLOCKS, BigBirdError,
                       EXPORTED_SYMBOLS, bigbird_attn_bwd, bigbird_attn_bwd_dropout, bigbird_attn_fwd,
                       bigbird_attn_fwd_dropout, bigbird_attn_fwd_static, bigbird_dropout_keep_mask,
                       bigbird_attn_workspace_bytes, bigbird_count_block_pairs,
@@ -12,7 +13,8 @@ from .binding import (BB_BF16, BB_F32, BB_GLOBAL_FIRST_LAST, BB_GLOBAL_LEADING, 
                       library_path, load_library, prepare_attn_bwd, prepare_attn_fwd)
 
 __all__ = [
-    "BB_BF16", "BB_F32", "BB_GLOBAL_FIRST_LAST", "BB_GLOBAL_LEADING", "BigBirdError",
+    "BB_BF16", "BB_F32", "BB_GLOBAL_FIRST_LAST", "BB_GLOBAL_LEADING", "BB_SKIP_PADDED_QUERY_BLOCKS",
+    "BigBirdError",
     "EXPORTED_SYMBOLS", "bigbird_attn_bwd", "bigbird_attn_bwd_dropout", "bigbird_attn_fwd",
     "bigbird_attn_fwd_dropout", "bigbird_attn_fwd_static", "bigbird_dropout_keep_mask",
     "bigbird_attn_workspace_bytes",

@@ -95,6 +95,8 @@ int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* L
                   const int32_t* rand_idx, const uint8_t* key_padding_mask, int B, int H, int n,
                   int d, int b, int g, int w, int r, float scale, int dtype, int global_mode,
                   const bb::Dropout& drop, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int skip_q = (global_mode & BB_SKIP_PADDED_QUERY_BLOCKS) != 0;
+  global_mode &= ~BB_SKIP_PADDED_QUERY_BLOCKS;
   int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
   if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
@@ -123,6 +125,7 @@ int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* L
   p.g = g; p.w = w; p.r = r; p.global_mode = global_mode;
   p.c = scale * bb::kLog2e;
   p.drop = drop;
+  p.skip_q = (skip_q && key_padding_mask) ? 1 : 0;
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   if (dtype == BB_BF16) {
     bb::Bf16Geom& q = p.geo;
@@ -259,7 +262,7 @@ extern "C" int bigbird_attn_fwd_static(const void* Q, const void* K, const void*
                                        const int32_t* rand_idx, const uint8_t* key_padding_mask, int B,
                                        int H, int n, int d, int b, int g, int w, int r, float scale,
                                        int dtype, int global_mode, void* hip_stream) {
-  int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
+  int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode & ~BB_SKIP_PADDED_QUERY_BLOCKS);
   if (st != BB_OK) return st;
   const size_t need = make_layout(B, H, n, b, g, w, r, 0).fwd_total;
   if (need > kStaticScratchBytes) {
@@ -285,6 +288,8 @@ int attn_bwd_impl(const void* Q, const void* K, const void* V, const void* O,
                   int H, int n, int d, int b, int g, int w, int r, float scale,
                   int dtype, int global_mode, const bb::Dropout& drop, void* workspace,
                   size_t workspace_bytes, void* hip_stream) {
+  const int skip_q = (global_mode & BB_SKIP_PADDED_QUERY_BLOCKS) != 0;
+  global_mode &= ~BB_SKIP_PADDED_QUERY_BLOCKS;
   int st = check_attn_shape(B, H, n, d, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
   if (dtype != BB_F32 && dtype != BB_BF16) return BB_ERR_DTYPE;
@@ -319,6 +324,7 @@ int attn_bwd_impl(const void* Q, const void* K, const void* V, const void* O,
   p.c = scale * bb::kLog2e;
   p.scale = scale;
   p.drop = drop;
+  p.skip_q = (skip_q && key_padding_mask) ? 1 : 0;
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   p.cq = (p.nb + bb::kChunk - 1) / bb::kChunk;
   p.kv_items_per_bh = g * p.cq + (p.nb - g);

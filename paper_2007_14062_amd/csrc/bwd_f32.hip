@@ -78,8 +78,11 @@ __global__ __launch_bounds__(kF32Threads) void bwd_f32_dq_kernel(BwdParams p) {
       dsum = __builtin_fmaf(gv[e], ov[e], dsum);
     }
   }
+  // a query block that was skipped (no valid position) behaves like rows without a valid key
+  const bool skip = p.skip_q && !block_has_valid_key(p.kmask, bi, p.n, j);
+  if (skip) dsum = 0.f;
   const float lse = p.LSE[qrow];
-  const float lse2 = (lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;  // no valid key: every P is 0
+  const float lse2 = (skip || lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;  // no valid key: every P is 0
   if (kg == 0) {
     p.Dvec[qrow] = dsum;
     p.Lvec[qrow] = lse2;

@@ -34,6 +34,7 @@ struct BwdParams {
   int cq;          // slices of the query-block list of a global key block: ceil(nb / 8)
   int kv_items_per_bh;  // g*cq + (nb - g)
   Dropout drop;    // attention dropout of the forward these gradients belong to (thr == 0: none)
+  int skip_q;      // query blocks without a valid position (in kmask) were not computed: no gradient through them
 };
 
 // Enqueues: the dQ kernel (which also computes the row sums D), the dK/dV kernel and the

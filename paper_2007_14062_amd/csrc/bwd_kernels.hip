@@ -70,8 +70,11 @@ void bwd_dq_kernel(BwdParams p) {
   const int lane = lane_id(), wv = threadIdx.x >> 6;
   const int hf = lane >> 5, col = lane & 31;
 
-  const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
-                                 it.chunk, klist);
+  // a query block that the forward did not compute (no valid position, and the caller asked for
+  // such blocks to be skipped): no key block, D = 0, probabilities 0
+  const bool skip = p.skip_q && key_valid_bits(p.kmask, bi, p.n, it.j) == 0;
+  const int cnt = skip ? 0 : build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
+                                            it.chunk, klist);
   __syncthreads();
   const int kl = klist[lane & (kChunkMax - 1)];
   auto key_block = [&](int i) { return __builtin_amdgcn_readlane(kl, i); };
@@ -115,9 +118,9 @@ void bwd_dq_kernel(BwdParams p) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) part += static_cast<float>(dob[ks][e]) * static_cast<float>(ob[e]);
     }
-    dsum = half_sum(part);
+    dsum = skip ? 0.f : half_sum(part);
     const float lse = p.LSE[qrow];
-    lse2 = (lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;
+    lse2 = (skip || lse == neg_inf()) ? __builtin_inff() : lse * kLog2e;
     if (it.chunk == 0 && hf == 0) {
       p.Dvec[qrow] = -dsum;  // negated: the other kernel starts its dP accumulators from it
       p.Lvec[qrow] = lse2;
@@ -308,7 +311,15 @@ void bwd_dkv_kernel(BwdParams p) {
     const int lo = chunk * kChunk;
     cnt = nb - lo < kChunk ? nb - lo : kChunk;
     if (cnt < 0) cnt = 0;
-    if (threadIdx.x < kChunk) jlist[threadIdx.x] = lo + threadIdx.x;
+    if (!p.skip_q) {
+      if (threadIdx.x < kChunk) jlist[threadIdx.x] = lo + threadIdx.x;
+    } else {
+      // without the query blocks that were not computed (both waves count, wave 0 writes)
+      const bool valid = lane < cnt && block_has_valid_key(p.kmask, bi, p.n, lo + lane);
+      const uint64_t m = __ballot(valid);
+      if (valid && wv == 0) jlist[mask_rank(m)] = lo + lane;
+      cnt = static_cast<int>(__popcll(m));
+    }
   } else {
     // global query blocks, then the window, then rows of rand_idx that name k
     const int32_t* tbl = p.rand_idx ? p.rand_idx + static_cast<size_t>(h) * nb * p.r : nullptr;
@@ -323,6 +334,7 @@ void bwd_dkv_kernel(BwdParams p) {
         j = k - pat.half() + (ci - p.g);
         valid = j >= 0 && j < nb && !pat.is_global(j);
       }
+      if (p.skip_q && valid) valid = block_has_valid_key(p.kmask, bi, p.n, j);
       const uint64_t m = __ballot(valid);
       const int rank = cnt + mask_rank(m);
       if (valid && rank < kMaxBwdBlocks && wv == 0) jlist[rank] = j;
@@ -335,6 +347,7 @@ void bwd_dkv_kernel(BwdParams p) {
         if (j < nb && !pat.is_global(j) && !pat.in_window(j, k)) {
           for (int t = 0; t < p.r; ++t) valid |= tbl[static_cast<size_t>(j) * p.r + t] == k;
         }
+        if (p.skip_q && valid) valid = block_has_valid_key(p.kmask, bi, p.n, j);
         const uint64_t m = __ballot(valid);
         const int rank = cnt + mask_rank(m);
         if (valid && rank < kMaxBwdBlocks && wv == 0) jlist[rank] = j;

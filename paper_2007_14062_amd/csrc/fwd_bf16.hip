@@ -429,6 +429,7 @@ struct Item {
   int cnt;             // key blocks in this slice
   int kl;              // the list: lane t holds entry t % 16
   bool any_partial;    // some listed block has padded keys inside
+  bool skipped;        // query block without a valid position, not to be computed (cnt = 0)
 };
 
 // Global addresses of an item's tiles (wave uniform, scalar arithmetic).
@@ -516,6 +517,21 @@ __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, 
   bool row_global;
   item_coords(p, w, sc, t, it, list_lo, list_len, row_global);
   const int bi = it.bh / p.H, h = it.bh % p.H;
+  it.skipped = false;
+  if (p.skip_q && key_valid_bits(p.kmask, bi, p.n, it.j) == 0) {
+    // the caller reads the mask as a query mask too, and no position of this block is valid:
+    // an item without key blocks (O = 0, LSE = -inf)
+    it.skipped = true;
+    it.any_partial = false;
+    it.kl = 0;
+    it.bh = __builtin_amdgcn_readfirstlane(it.bh);
+    it.j = __builtin_amdgcn_readfirstlane(it.j);
+    it.chunk = __builtin_amdgcn_readfirstlane(it.chunk);
+    it.nchunks = __builtin_amdgcn_readfirstlane(it.nchunks);
+    it.slot = __builtin_amdgcn_readfirstlane(it.slot);
+    it.cnt = 0;
+    return;
+  }
   // Non-global rows: the table row comes through the scalar data path and the list is made
   // without a vector memory access.  A padding mask is then applied to the finished list, lane i
   // looking at block i (one round trip to memory for the whole list) -- for rows of one slice,
@@ -849,6 +865,19 @@ __device__ __forceinline__ void store_partial(const FwdParams& p, const WaveCtx&
   }
 }
 
+// O = 0 and LSE = -inf for the 64 rows of a query block that is not computed (whole rows, 16 bytes
+// per lane, straight from registers).
+__device__ __forceinline__ void store_zero_rows_bf16(const FwdParams& p, const Item& it) {
+  const size_t row_blk = static_cast<size_t>(it.bh) * p.n + it.j * kBlk;
+  const int lane = lane_id();
+  p.LSE[row_blk + lane] = neg_inf();
+  __bf16* orow = static_cast<__bf16*>(p.O) + row_blk * kDim;
+  const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int ii = 0; ii < 8; ++ii)
+    __builtin_nontemporal_store(z, reinterpret_cast<u32x4*>(orow + (ii * 8 + (lane >> 3)) * kDim + (lane & 7) * 8));
+}
+
 // The kernel's argument block as the cold functions below see it.  A reference to the kernel's own
 // copy would move that copy, and every later use of it in the hot loop, into scratch memory, and the
 // kernel-argument segment pointer is only defined inside the kernel itself.  So the kernel hands its
@@ -1089,6 +1118,10 @@ void fwd_kernel_bf16(FwdParams p) {
       if (it.cnt > 0 && !it.any_partial) {
         found = t;
         break;
+      }
+      if (it.skipped && it.nchunks == 1) {  // nothing to compute: its rows are written here
+        store_zero_rows_bf16(p, it);
+        continue;
       }
       push_redo(t);
     }

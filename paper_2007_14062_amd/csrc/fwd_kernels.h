@@ -44,6 +44,7 @@ struct FwdParams {
   // (slots first), then cmb_s_rows non-global rows of cmb_s_n slices; slots_per_bh in total
   int cmb_g_rows, cmb_g_n, cmb_s_rows, cmb_s_n, slots_per_bh;
   Dropout drop;  // attention dropout (thr == 0: none)
+  int skip_q;    // query blocks without a valid position (in kmask) are not computed: O = 0, LSE = -inf
 };
 
 // Enqueues the fused forward kernel and, if any row is split, the merge kernel.

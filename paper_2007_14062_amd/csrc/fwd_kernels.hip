@@ -58,8 +58,11 @@ __global__ __launch_bounds__(kThreads) void fwd_kernel_f32(FwdParams p) {
   const int lane = lane_id(), wv = threadIdx.x >> 6;
   const int hf = lane >> 5, col = lane & 31;
 
-  const int cnt = build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
-                                 it.chunk, klist);
+  // (a query block without a valid position, if the caller asked for those to be skipped, is an
+  // empty row: O = 0, LSE = -inf through the usual end of an item)
+  const bool skip = p.skip_q && key_valid_bits(p.kmask, bi, p.n, it.j) == 0;
+  const int cnt = skip ? 0 : build_key_list(pat, p.rand_idx, p.r, p.kmask, p.n, bi, h, it.j, it.row_global,
+                                            it.chunk, klist);
   __syncthreads();
 
   const size_t bh_row0 = static_cast<size_t>(it.bh) * p.n;    // first row of this (batch, head)

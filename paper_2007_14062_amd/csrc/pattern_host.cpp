@@ -103,6 +103,8 @@ extern "C" int64_t bigbird_count_block_pairs(const int32_t* rand_idx_host,
                                              const uint8_t* key_mask_host, int B, int H, int n,
                                              int b, int g, int w, int r, int global_mode) {
   if (!rand_idx_host && H > 0 && r > 0) return BB_ERR_NULL;
+  const bool skip_q = (global_mode & BB_SKIP_PADDED_QUERY_BLOCKS) != 0 && key_mask_host;
+  global_mode &= ~BB_SKIP_PADDED_QUERY_BLOCKS;
   int st = bb::check_pattern_args(H, n, b, g, w, r, global_mode);
   if (st != BB_OK) return st;
   if (B < 0) return BB_ERR_SHAPE;
@@ -121,6 +123,7 @@ extern "C" int64_t bigbird_count_block_pairs(const int32_t* rand_idx_host,
     }
     for (int h = 0; h < H; ++h) {
       for (int j = 0; j < nb; ++j) {
+        if (skip_q && !valid[j]) continue;  // a query block without a valid position is not computed
         std::fill(seen.begin(), seen.end(), 0);
         if (pat.is_global(j)) {
           std::fill(seen.begin(), seen.end(), 1);

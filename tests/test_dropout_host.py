@@ -38,3 +38,22 @@ def test_bad_rates_and_ranges_are_refused():
     assert lib.bigbird_attn_bwd_dropout(*args_b, ctypes.c_float(-0.5), 1, z, 0, z) == -2
     # a valid rate goes on to the usual checks (NULL tensors)
     assert lib.bigbird_attn_fwd_dropout(*args_f, ctypes.c_float(0.1), 1, z, 0, z) == -1
+
+
+def test_pair_count_with_skipped_query_blocks_equals_the_oracle_count():
+    import oracle
+    H, n, b, g, w, r, B = 3, 1024, 64, 2, 3, 3, 3
+    nb = n // b
+    ridx = bb.bigbird_make_rand_idx(H, n, b, g, w, r, 4)
+    km = np.ones((B, n), dtype=np.uint8)
+    km[0, 700:] = 0
+    km[1, 128:320] = 0
+    km[2, :] = 1
+    for flag in (0, bb.BB_SKIP_PADDED_QUERY_BLOCKS):
+        got = bb.bigbird_count_block_pairs(ridx, km, B, H, n, b, g, w, r, flag)
+        want = sum(oracle.count_block_pairs(ridx, n, b, g, w,
+                                            key_block_valid=km[bi].reshape(nb, b).any(axis=1),
+                                            skip_padded_query_blocks=bool(flag)) for bi in range(B))
+        assert got == want
+    assert bb.bigbird_count_block_pairs(ridx, None, B, H, n, b, g, w, r, bb.BB_SKIP_PADDED_QUERY_BLOCKS) == \
+        bb.bigbird_count_block_pairs(ridx, None, B, H, n, b, g, w, r)
