@@ -14,6 +14,8 @@ inline size_t round_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct WorkspaceLayout {
   size_t part_o = 0, part_ml = 0;  // forward: partial triples of split rows
+  size_t counters = 0;             // forward: item counters of the dies (only if anything is carved at all)
+  bool has_counters = false;
   size_t fwd_total = 0;
   // backward (its own carving of the same buffer): row sums, scaled LSE, partial gradients
   size_t dvec = 0, lvec = 0, part_dq = 0, part_dk = 0, part_dv = 0;
@@ -41,6 +43,11 @@ WorkspaceLayout make_layout(int B, int H, int n, int b, int g, int w, int r, int
   off += round_up(slots * bb::kBlk * bb::kDim * sizeof(float));
   L.part_ml = off;
   off += round_up(slots * 2 * bb::kBlk * sizeof(float));
+  if (off > 0) {
+    L.counters = off;
+    L.has_counters = true;
+    off += round_up(bb::kXcd * bb::kCounterStride * sizeof(int));
+  }
   L.fwd_total = off;
   L.total = off;
   if (need_bwd) {
@@ -126,6 +133,13 @@ int attn_fwd_impl(const void* Q, const void* K, const void* V, void* O, float* L
   p.c = scale * bb::kLog2e;
   p.drop = drop;
   p.skip_q = (skip_q && key_padding_mask) ? 1 : 0;
+  // When query blocks may be skipped, a fixed share of the items can be anything from all skipped
+  // to all computed: the waves of the bf16 kernel then claim their items from a counter per die.
+  // (Without skipped blocks claiming measured no gain over fixed shares at the key-padding
+  // workload -- 60.6 against 61.1 us with its extra launch; with dropout every item is the same
+  // slow path.)
+  p.counters = L.has_counters ? reinterpret_cast<int*>(ws + L.counters) : nullptr;
+  p.dyn = (dtype == BB_BF16 && p.skip_q && drop.thr == 0 && p.counters) ? 1 : 0;
   p.split = bb::make_row_split(p.BH, p.nb, g, w, r);
   if (dtype == BB_BF16) {
     bb::Bf16Geom& q = p.geo;

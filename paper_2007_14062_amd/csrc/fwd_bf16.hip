@@ -474,10 +474,30 @@ __device__ __forceinline__ void scalar_load4(const int32_t* row_, int o0, int o1
       : "memory");
 }
 
+// Does block j of batch entry bi hold a valid position?  The 64 mask bytes come through the scalar
+// data path (request and wait in one statement, on the scalar counter): no vector memory wait, which
+// would also wait for the tile loads in flight and for the stores of rows just written.
+__device__ __forceinline__ bool block_any_valid_scalar(const uint8_t* kmask, int bi, int n, int j) {
+  typedef __attribute__((ext_vector_type(16))) unsigned int u32x16;
+  const char* ptr = uniform_ptr(reinterpret_cast<const char*>(kmask) + static_cast<size_t>(bi) * n + static_cast<size_t>(j) * kBlk);
+  u32x16 v;
+  asm volatile(
+      "s_load_dwordx16 %0, %1, 0x0\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(v)
+      : "s"(ptr)
+      : "memory");
+  unsigned any = 0;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) any |= v[e];
+  return any != 0;
+}
+
 // Item number -> item with its key-block list (for a global-row workgroup: the wave's share of
 // the row).  All loads here are waited for before the function returns (scalar loads inside
 // their asm statement, the others by the compiler), so tile loads in flight are at most delayed.
 // Its first part: which row, which slice of the row's list (arithmetic only, no memory access).
+template <bool kX>
 __device__ __forceinline__ void item_coords(const FwdParams& p, const WaveCtx& w, const Sched& sc, int t, Item& it,
                                             int& list_lo, int& list_len, bool& row_global) {
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
@@ -494,6 +514,9 @@ __device__ __forceinline__ void item_coords(const FwdParams& p, const WaveCtx& w
     list_lo = (u * kFwdWaves + w.wv) * geo.gw_len;
     list_len = geo.gw_len;
   } else {
+    // (item order inside a die: slice by slice, so that a slice's K and V stay in the L2 while its
+    // rows run -- also when items are claimed: row by row across the slices, which would put the
+    // rows that are not computed last, measured 52.8 against 49.2 us at the key-padding workload)
     it.bh = (t / geo.n_sitems) * kXcd + sc.xcd;
     const int sitem = t % geo.n_sitems;
     row_global = false;
@@ -510,15 +533,18 @@ __device__ __forceinline__ const char* query_tile(const FwdParams& p, int bh, in
   return static_cast<const char*>(p.Q) + (static_cast<size_t>(bh) * p.n + static_cast<size_t>(j) * kBlk) * (kDim * 2);
 }
 
+// kX (here and below): the instance of the kernel that serves attention dropout and skipped query
+// blocks.  The plain instance holds none of that code, so its registers and schedule are its own.
+template <bool kX>
 __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, const Sched& sc, int t, Item& it) {
   const Pattern pat{p.nb, p.g, p.w, p.global_mode};
   const int lane = lane_again(w.lane);
   int list_lo, list_len;
   bool row_global;
-  item_coords(p, w, sc, t, it, list_lo, list_len, row_global);
+  item_coords<kX>(p, w, sc, t, it, list_lo, list_len, row_global);
   const int bi = it.bh / p.H, h = it.bh % p.H;
   it.skipped = false;
-  if (p.skip_q && key_valid_bits(p.kmask, bi, p.n, it.j) == 0) {
+  if (kX && p.skip_q && !block_any_valid_scalar(p.kmask, __builtin_amdgcn_readfirstlane(bi), p.n, __builtin_amdgcn_readfirstlane(it.j))) {
     // the caller reads the mask as a query mask too, and no position of this block is valid:
     // an item without key blocks (O = 0, LSE = -inf)
     it.skipped = true;
@@ -560,7 +586,7 @@ __device__ __forceinline__ void make_item(const FwdParams& p, const WaveCtx& w, 
   asm volatile("" ::: "memory");
   it.kl = w.klist[lane & (kGlobalWaveLen - 1)];
   asm volatile("" ::: "memory");
-  it.any_partial = p.drop.thr != 0;  // attention dropout is applied on the slow path only
+  it.any_partial = kX && p.drop.thr != 0;  // attention dropout is applied on the slow path only
   if (p.kmask) {
     bool any_valid = false, any_padded = false;
     if (lane < it.cnt) block_mask_flags(p.kmask, bi, p.n, it.kl, any_valid, any_padded);
@@ -702,6 +728,7 @@ __device__ __forceinline__ void fast_item(const PairCtx& cx, const StraightOffse
 // with synchronous tile loads: the path of items with padded keys inside a block and the
 // fallback for items whose row sums left the safe range of the reference-free path.  Leaves m_ref (exponent
 // units), this lane's share of the row sums and O~.  Any load still in flight lands first.
+template <bool kX>
 __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffsets& so, const TransposedOffsets& to,
                                           const bf16x8 (&qb)[2][4], const FwdParams& p, const Item& item,
                                           f32x16 (&o)[2][2], float (&l_run)[2], float (&m_ref)[2]) {
@@ -716,7 +743,7 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
   // attention dropout (all items of a call with dropout come here): the keys of this lane's two
   // rows of the keep mask
   uint32_t drop_rk[2] = {0u, 0u};
-  if (p.drop.thr) {
+  if (kX && p.drop.thr) {
     const uint32_t row0 = static_cast<uint32_t>(item.bh) * static_cast<uint32_t>(p.n) + item.j * kBlk + (lane_id() & 31);
 #pragma unroll
     for (int q = 0; q < 2; ++q) drop_rk[q] = drop_row_key(p.drop, row0 + q * 32);
@@ -774,7 +801,7 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
             const float p0 = fast_exp2(s[t][r] - m_use), p1 = fast_exp2(s[t][r + 1] - m_use);
             bf16x2 pk = {static_cast<__bf16>(p0), static_cast<__bf16>(p1)};
             l_run[q] += p0 + p1;  // (the row sums are those of the undropped probabilities)
-            if (p.drop.thr) {
+            if (kX && p.drop.thr) {
               // registers r, r + 1 are keys 2m, 2m + 1: one word of the mask
               const uint32_t key = static_cast<uint32_t>(kblock * kBlk + t * 32 + acc_row(r, cx.hf));
               const uint32_t wd = drop_word(drop_rk[q], key >> 1);
@@ -905,14 +932,16 @@ __device__ __forceinline__ const void* kernel_kernargs() {
 // of items with padded keys inside a block or without any key block, and of items whose row sums
 // left the safe range of the pipelined path.  A function of its own, so that its registers are
 // not the persistent loop's problem.
+template <bool kX>
 __device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t) {
   const FwdParams p = params_from(kernargs);
   const WaveCtx w(p.c);
-  const Sched sc(p);
+  Sched sc(p);
+  sc.global_wg = false;  // (a wave of a global-row workgroup that went on to claim other items)
   const StraightOffsets so(w.lane);
   const TransposedOffsets to(w.lane);
   Item it;
-  make_item(p, w, sc, t, it);
+  make_item<kX>(p, w, sc, t, it);
   wait_tile_loads<0>();
   bf16x8 qb[2][4];
   f32x16 o[2][2];
@@ -923,14 +952,14 @@ __device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t)
     so.read(w.lds_v, qb);
     wait_lds_reads();
     }
-  slow_item(w.cx, so, to, qb, p, it, o, l_run, m_ref);
+  slow_item<kX>(w.cx, so, to, qb, p, it, o, l_run, m_ref);
 #pragma unroll
   for (int q = 0; q < 2; ++q) l_tot[q] = half_sum(l_run[q]);
   if (it.nchunks == 1) {
     float inv[2], lse[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-      inv[q] = l_tot[q] > 0.f ? p.drop.rs / l_tot[q] : 0.f;  // (rs: 1, or the dropout scale)
+      inv[q] = l_tot[q] > 0.f ? (kX ? p.drop.rs : 1.f) / l_tot[q] : 0.f;  // (rs: 1, or the dropout scale)
       lse[q] = l_tot[q] > 0.f ? (m_ref[q] + fast_log2(l_tot[q])) * kLn2 : neg_inf();
     }
     store_rows_bf16(p, w, it, o, inv, lse);
@@ -944,6 +973,7 @@ __device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t)
 // real call would start by saving a hundred callee-saved vector registers to scratch memory
 // (11 MB of HBM writes per launch at the BERT-base size, measured) for a caller that has nothing
 // in them.
+template <bool kX>
 __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
   const WaveCtx w(p.c);
   const Sched sc(p);
@@ -954,7 +984,7 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
   const long long rt0 = __builtin_amdgcn_s_memrealtime();
 #endif
   Item cur;
-  make_item(p, w, sc, 0, cur);
+  make_item<kX>(p, w, sc, 0, cur);
   bf16x8 qb[2][4], ka[2][4];
   f32x16 o[2][2];
   float m_ref[2] = {0.f, 0.f};  // reference exponents (base-2 units); halves agree
@@ -971,7 +1001,7 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
       for (int q = 0; q < 2; ++q) bad |= !(l_tot[q] >= kSumLo && l_tot[q] <= kSumHi);
     }
     if (__any(bad)) {
-      slow_item(w.cx, so, to, qb, p, cur, o, l_run, m_ref);
+      slow_item<kX>(w.cx, so, to, qb, p, cur, o, l_run, m_ref);
 #pragma unroll
       for (int q = 0; q < 2; ++q) l_tot[q] = half_sum(l_run[q]);
     }
@@ -1034,7 +1064,7 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
   }
   const size_t row = row_blk + q;
   if (cur.nchunks == 1) {
-    const float inv = L > 0.f ? p.drop.rs / L : 0.f;  // (rs: 1, or the dropout scale)
+    const float inv = L > 0.f ? (kX ? p.drop.rs : 1.f) / L : 0.f;  // (rs: 1, or the dropout scale)
     if (part == 0) p.LSE[row] = L > 0.f ? (M + fast_log2(L)) * kLn2 : neg_inf();
     bf16x8 v0, v1;
 #pragma unroll
@@ -1063,12 +1093,27 @@ __device__ __forceinline__ void global_row_workgroup(const FwdParams& p) {
 
 }  // namespace
 
+// The item counters of the dies start every launch at zero (a kernel, not a memset: the call may
+// be under graph capture).
+__global__ void zero_counters_kernel(int* counters) {
+  if (threadIdx.x < kXcd) counters[threadIdx.x * kCounterStride] = 0;
+}
+
+template <bool kX>
 __global__ __launch_bounds__(kFwdThreads) __attribute__((amdgpu_waves_per_eu(2)))
 void fwd_kernel_bf16(FwdParams p) {
-  const Sched sc(p);
+  Sched sc(p);
+  // dyn: after its first piece of work a wave claims items from its die's counter (zeroed before
+  // the launch) instead of taking every wave_stride-th one: with a padding mask items differ in
+  // length and some are not computed at all.  The waves of a global-row workgroup then join in
+  // when their row is done.
+  const bool dyn = kX && p.dyn != 0;
+  const bool was_global = sc.global_wg;
   if (sc.global_wg) {
-    if ((sc.wg / p.geo.g_wgs) * kXcd + sc.xcd < static_cast<unsigned>(p.BH)) global_row_workgroup(p);
-    return;
+    if ((sc.wg / p.geo.g_wgs) * kXcd + sc.xcd < static_cast<unsigned>(p.BH)) global_row_workgroup<kX>(p);
+    if (!dyn) return;
+    __syncthreads();  // the merge has read the other waves' LDS regions; from here on each wave's is its own
+    sc.global_wg = false;
   }
   const WaveCtx w(p.c);
   const PairCtx& cx = w.cx;
@@ -1078,7 +1123,21 @@ void fwd_kernel_bf16(FwdParams p) {
   const StraightOffsets so(lane);
   const TransposedOffsets to(lane);
   const int n_items_die = sc.n_items_die, wave_stride = sc.wave_stride;
-  const int t_item = static_cast<int>(sc.wg - sc.n_gpart) * kFwdWaves + w.wv;  // first item of this wave
+  // the die's next unclaimed item (tickets start after the items the persistent waves begin with)
+  auto claim = [&]() {
+    int c = 0;
+    // Executed in the die's L2, which all claimers of this counter share (a counter per die, a
+    // cache line each).  Were two dies ever to work on one counter, each would see its own copy:
+    // items done twice with the same result, none left out.
+    if (lane == 0)
+      c = __hip_atomic_fetch_add(p.counters + sc.xcd * kCounterStride, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    c = __builtin_amdgcn_readfirstlane(c);
+    // (a counter that has run far past the end must not wrap the sum)
+    return c < n_items_die ? wave_stride + c : n_items_die;
+  };
+  int t_first = static_cast<int>(sc.wg - sc.n_gpart) * kFwdWaves + w.wv;  // first item of this wave
+  if (dyn && was_global) t_first = claim();
+  const int t_item = __builtin_amdgcn_readfirstlane(t_first);
   if (t_item >= n_items_die) return;
 
   bf16x8 qb[2][4];  // Q^T operands (B of S^T = K Q^T): lane holds query `col` (+32 for tile B),
@@ -1113,20 +1172,28 @@ void fwd_kernel_bf16(FwdParams p) {
   // the next item at or after t that takes the pipelined path (others go to the list)
   auto next_fast = [&](int t, Item& it) {
     int found = -1;
-    for (; t < n_items_die; t += wave_stride) {
-      make_item(p, w, sc, t, it);
+    while (t < n_items_die) {
+      make_item<kX>(p, w, sc, t, it);
       if (it.cnt > 0 && !it.any_partial) {
         found = t;
         break;
       }
-      if (it.skipped && it.nchunks == 1) {  // nothing to compute: its rows are written here
+      if (kX && it.skipped && it.nchunks == 1) {  // nothing to compute: its rows are written here
         store_zero_rows_bf16(p, it);
-        continue;
+      } else {
+        push_redo(t);
       }
-      push_redo(t);
+      if (dyn) {
+        if (n_redo >= 64) break;  // the list is full: this wave takes no more items, the others do
+        t = claim();
+      } else {
+        t += wave_stride;
+      }
     }
     return __builtin_amdgcn_readfirstlane(found);
   };
+  // where the search for the item after item t begins
+  auto successor = [&](int t) { return dyn ? (n_redo < 64 ? claim() : n_items_die) : t + wave_stride; };
 
   // cur: the item in work; nxt: the one after it (its list is needed before cur's last pairs,
   // which fetch its first tiles); nn: the one after that, built while few loads are in flight.
@@ -1136,7 +1203,7 @@ void fwd_kernel_bf16(FwdParams p) {
   {
     int lo_, len_;
     bool rg_;
-    item_coords(p, w, sc, t_item, cur, lo_, len_, rg_);
+    item_coords<kX>(p, w, sc, t_item, cur, lo_, len_, rg_);
     tile_load_async_wave(query_tile(p, __builtin_amdgcn_readfirstlane(cur.bh), __builtin_amdgcn_readfirstlane(cur.j)),
                          cx.lds_k_a, cx.voff);
   }
@@ -1168,7 +1235,8 @@ void fwd_kernel_bf16(FwdParams p) {
     };
     // pairs this wave still has to do, roughly (for its issue priority)
     const int pairs_per_item = p.geo.cs > 1 ? kGlobalWaveLen : (p.g + p.w + p.r < kGlobalWaveLen ? p.g + p.w + p.r : kGlobalWaveLen);
-    int rem_pairs = __builtin_amdgcn_readfirstlane(((n_items_die - t_cur + wave_stride - 1) / wave_stride) * pairs_per_item);
+    int rem_pairs = dyn ? 0  // (unknown when items are claimed: every wave at the same priority)
+                        : __builtin_amdgcn_readfirstlane(((n_items_die - t_cur + wave_stride - 1) / wave_stride) * pairs_per_item);
 
     // start of the first item.  Skipped items ahead of it: the request above was for another row.
     wait_tile_loads<0>();
@@ -1189,7 +1257,7 @@ void fwd_kernel_bf16(FwdParams p) {
 #ifdef BB_STAMPS
     st_t[2] = __builtin_readcyclecounter() - tprev;
 #endif
-    t_nxt = next_fast(t_cur + wave_stride, nxt);  // (scalar loads only, unless there is a padding mask)
+    t_nxt = next_fast(successor(t_cur), nxt);  // (scalar loads only, unless there is a padding mask)
     TileStreams ts(p, cur, t_nxt >= 0 ? &nxt : nullptr, lane_again(lane));
     int cnt = __builtin_amdgcn_readfirstlane(cur.cnt);  // pairs of the item in work
       reset_item_state();
@@ -1234,7 +1302,7 @@ void fwd_kernel_bf16(FwdParams p) {
       int t_nn = -1;
       BB_STAMP(2);
       if (t_nxt >= 0) {
-        t_nn = next_fast(t_nxt + wave_stride, nn);
+        t_nn = next_fast(successor(t_nxt), nn);
         BB_STAMP(3);
         // The next item's query tile is in the K buffer, its first K tile in the V buffer (the
         // second half may still be landing).  Both go to registers, its first V tile is requested,
@@ -1297,13 +1365,20 @@ void fwd_kernel_bf16(FwdParams p) {
 #endif
 
   // ---- the listed items, by the classical recurrence
-  for (int u = 0; u < n_redo; ++u) redo_item(kernel_kernargs(), __builtin_amdgcn_readlane(redo, u));
+  for (int u = 0; u < n_redo; ++u) redo_item<kX>(kernel_kernargs(), __builtin_amdgcn_readlane(redo, u));
 }
 
 int launch_fwd_bf16_main(const FwdParams& p, hipStream_t stream) {
   const unsigned grid = static_cast<unsigned>(kXcd) * (p.geo.bh_rounds * p.geo.g_wgs + p.geo.p_wgs);
   if (grid == 0) return BB_OK;
-  hipLaunchKernelGGL(fwd_kernel_bf16, dim3(grid), dim3(kFwdThreads), 0, stream, p);
+  if (p.dyn) {
+    hipLaunchKernelGGL(zero_counters_kernel, dim3(1), dim3(64), 0, stream, p.counters);
+    if (hipGetLastError() != hipSuccess) return BB_ERR_LAUNCH;
+  }
+  if (p.drop.thr != 0 || p.skip_q || p.dyn)
+    hipLaunchKernelGGL(fwd_kernel_bf16<true>, dim3(grid), dim3(kFwdThreads), 0, stream, p);
+  else
+    hipLaunchKernelGGL(fwd_kernel_bf16<false>, dim3(grid), dim3(kFwdThreads), 0, stream, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) {
     fprintf(stderr, "bigbird: launch of fwd_kernel_bf16 failed: %s\n", hipGetErrorString(e));

@@ -14,6 +14,7 @@ namespace bb {
 // A global row longer than 64 key blocks takes several workgroups whose merged partial
 // results go through the merge kernel, as do sparse rows with more than one slice.
 constexpr int kGlobalWaveLen = 16;  // most key blocks a wave of a global workgroup takes
+constexpr int kCounterStride = 32;  // ints between the item counters of two dies (a 128-byte line each)
 struct Bf16Geom {
   int gw_len;    // key blocks per wave of a global workgroup: 16, or 8 when the whole grid fits
                  // the chip at once (then the global rows alone would set the run time)
@@ -45,6 +46,8 @@ struct FwdParams {
   int cmb_g_rows, cmb_g_n, cmb_s_rows, cmb_s_n, slots_per_bh;
   Dropout drop;  // attention dropout (thr == 0: none)
   int skip_q;    // query blocks without a valid position (in kmask) are not computed: O = 0, LSE = -inf
+  int dyn;       // bf16 kernel: waves claim their items after the first from the die's counter
+  int* counters; // [8 * kCounterStride] one per die, zeroed by a small launch before the kernel (dyn != 0 only)
 };
 
 // Enqueues the fused forward kernel and, if any row is split, the merge kernel.
