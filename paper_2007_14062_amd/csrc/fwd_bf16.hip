@@ -930,11 +930,9 @@ __device__ __forceinline__ const void* kernel_kernargs() {
 
 // One non-global item by the classical recurrence, from its first load to its last store: the path
 // of items with padded keys inside a block or without any key block, and of items whose row sums
-// left the safe range of the pipelined path.  A function of its own, so that its registers are
-// not the persistent loop's problem.
+// left the safe range of the pipelined path, and of every item under attention dropout.
 template <bool kX>
-__device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t) {
-  const FwdParams p = params_from(kernargs);
+__device__ __forceinline__ void item_by_recurrence(const FwdParams& p, int t) {
   const WaveCtx w(p.c);
   Sched sc(p);
   sc.global_wg = false;  // (a wave of a global-row workgroup that went on to claim other items)
@@ -966,6 +964,16 @@ __device__ __attribute__((noinline)) void redo_item(const void* kernargs, int t)
   } else {
     store_partial(p, w, it, o, m_ref, l_tot);
   }
+}
+
+// The persistent loop's list of such items (lane u of `redo` holds the u-th item), as a called
+// function: its registers are not that loop's problem.  One call for the whole list: a call saves
+// and restores the callee-saved registers in scratch memory, about 50 KB per wave, which per item
+// was most of the time of launches in which many items come here.
+template <bool kX>
+__device__ __attribute__((noinline)) void redo_items(const void* kernargs, int redo, int n_redo) {
+  const FwdParams p = params_from(kernargs);
+  for (int u = 0; u < n_redo; ++u) item_by_recurrence<kX>(p, __builtin_amdgcn_readlane(redo, u));
 }
 
 // One global query block by a whole workgroup: 16 key blocks per wave, the four waves' (m, l, O~)
@@ -1135,6 +1143,13 @@ void fwd_kernel_bf16(FwdParams p) {
     // (a counter that has run far past the end must not wrap the sum)
     return c < n_items_die ? wave_stride + c : n_items_die;
   };
+  if (kX && p.drop.thr != 0) {
+    // attention dropout: every item takes the per-item path, so there is no stream to run and no
+    // list to keep -- wave w does the die's items w, w + wave_stride, ... one after the other
+    for (int t = static_cast<int>(sc.wg - sc.n_gpart) * kFwdWaves + w.wv; t < n_items_die; t += wave_stride)
+      item_by_recurrence<kX>(p, __builtin_amdgcn_readfirstlane(t));
+    return;
+  }
   int t_first = static_cast<int>(sc.wg - sc.n_gpart) * kFwdWaves + w.wv;  // first item of this wave
   if (dyn && was_global) t_first = claim();
   const int t_item = __builtin_amdgcn_readfirstlane(t_first);
@@ -1365,7 +1380,7 @@ void fwd_kernel_bf16(FwdParams p) {
 #endif
 
   // ---- the listed items, by the classical recurrence
-  for (int u = 0; u < n_redo; ++u) redo_item<kX>(kernel_kernargs(), __builtin_amdgcn_readlane(redo, u));
+  if (n_redo > 0) redo_items<kX>(kernel_kernargs(), redo, n_redo);
 }
 
 int launch_fwd_bf16_main(const FwdParams& p, hipStream_t stream) {
