@@ -748,23 +748,29 @@ __device__ __forceinline__ void slow_item(const PairCtx& cx, const StraightOffse
 #pragma unroll
     for (int q = 0; q < 2; ++q) drop_rk[q] = drop_row_key(p.drop, row0 + q * 32);
   }
-  for (int i = 0; i < item.cnt; ++i) {
-    const int kblock = __builtin_amdgcn_readlane(item.kl, i);
-    uint64_t vbits = ~0ull;
-    if (p.kmask) vbits = key_valid_bits(p.kmask, item.bh / p.H, p.n, kblock);
+  // The tiles of pair i + 1 are requested as soon as those of pair i sit in registers, and land
+  // under pair i's arithmetic.
+  auto request_tiles = [&](int i) {
     const char* kt = it.ktile(i);
     const char* vt = it.vtile(i);
     half_load_async(kt, cx.lds_k_a, 0, cx.voff);
     half_load_async(kt, cx.lds_k_a, 1, cx.voff);
     half_load_async(vt, cx.lds_v_a, 0, cx.voff);
     half_load_async(vt, cx.lds_v_a, 1, cx.voff);
+  };
+  if (item.cnt > 0) request_tiles(0);
+  for (int i = 0; i < item.cnt; ++i) {
+    const int kblock = __builtin_amdgcn_readlane(item.kl, i);
+    uint64_t vbits = ~0ull;
+    if (p.kmask) vbits = key_valid_bits(p.kmask, item.bh / p.H, p.n, kblock);
     wait_tile_loads<0>();
     bf16x8 ka[2][4], va[2][2][2];
     read_k_half(so, cx.lds_k, 0, ka[0]);
     read_k_half(so, cx.lds_k, 1, ka[1]);
     read_v_half(to, cx.lds_v, 0, va[0]);
     read_v_half(to, cx.lds_v, 1, va[1]);
-    wait_lds_reads();  // the buffers are overwritten by the next iteration's loads
+    wait_lds_reads();  // the buffers are free again
+    if (i + 1 < item.cnt) request_tiles(i + 1);
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       f32x16 s[2];
