@@ -46,6 +46,12 @@
 //     that neither read pattern has bank conflicts.
 //   * The two waves of a SIMD get their issue priority from the pairs they still have to
 //     do, so that they finish together (set_issue_priority).
+//   * Two instances of the kernel.  fwd_kernel_bf16<false> is everything above and nothing else.
+//     fwd_kernel_bf16<true> is launched only when a call asks for attention dropout (every item
+//     then takes the per-item path, in a plain loop, where the keep mask of dropout.h is applied
+//     to the probabilities that multiply V), or for fully padded query blocks to be skipped
+//     (BB_SKIP_PADDED_QUERY_BLOCKS: their rows are written as zeros and the waves claim the
+//     other items from a counter per die, global-row waves included once their row is done).
 // -DBB_STAMPS builds a development variant that writes per-wave time stamps into the
 // partial-result workspace (which must then hold 128 bytes per wave of the launch); the
 // library proper is built without it.
