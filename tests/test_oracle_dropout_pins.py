@@ -219,3 +219,42 @@ def test_row_sums_of_p_dp_equal_do_dot_o():
     P /= P.sum(axis=1, keepdims=True)
     dP = np.where(keep_mask(seed, 0, n, p), dropout_scale(p), 0.0) * (dO[0, 0] @ V[0, 0].T)
     assert np.abs((P * dP).sum(axis=1) - (dO[0, 0] * O[0, 0]).sum(axis=1)).max() < 1e-12
+
+
+def test_one_flipped_mask_bit_moves_the_counting_inputs_by_a_whole_step(monkeypatch):
+    """The inputs of tests/test_dropout_mask_exact.py (uniform softmax, one-hot rows) make every
+    output count kept pairs: a mistake planted here, one flipped bit of the oracle's mask, moves
+    O, dV, dQ and dK by about one step each -- four times that test's tolerance."""
+    import oracle.dropout as od
+    B, H, n, b, g, w, r = 1, 2, 1024, 64, 2, 3, 3
+    scale, p, seed = 0.125, 0.1, 0xC0FFEE1234
+    ridx = oracle.make_rand_idx(H, n, b, g, w, r, 21)
+    step = dropout_scale(p) / n
+    oh = np.zeros((B, H, n, 64))
+    oh[:, :, np.arange(n), np.arange(n) % 64] = 1.0
+    z, ones = np.zeros((B, H, n, 64)), np.ones((B, H, n, 64))
+    rnd = _rand((B, H, n, 64), 3)
+
+    def run():
+        return (od.attn_fwd_dropout(z, rnd, oh, ridx, b, g, w, scale, p, seed)[0],
+                od.attn_bwd_dropout(z, rnd, oh, oh, ridx, b, g, w, scale, p, seed)[2],
+                od.attn_bwd_dropout(z, oh, ones, ones / 64, ridx, b, g, w, scale, p, seed)[0],
+                od.attn_bwd_dropout(oh, z, ones, ones / 64, ridx, b, g, w, scale, p, seed)[1])
+
+    base = run()
+    i, j = 5, 700                      # a global row (the smallest step) and some key
+    orig = od.keep_mask
+
+    def flipped(seed_, bh, n_, p_, rows=None):
+        M = orig(seed_, bh, n_, p_, rows).copy()
+        if bh == 1:
+            rr = np.arange(n_) if rows is None else np.asarray(rows)
+            k = np.flatnonzero(rr == i)
+            if len(k):
+                M[k[0], j] = ~M[k[0], j]
+        return M
+
+    monkeypatch.setattr(od, "keep_mask", flipped)
+    new = run()
+    for x, y, s in zip(new, base, (step, step, scale * step, scale * step)):
+        assert np.abs(x - y).max() > 0.9 * s
